@@ -1,0 +1,314 @@
+"""CPU oracle for the DPPO loss hot path -- TEST INFRASTRUCTURE ONLY.
+
+A plain, slow, fp64 NumPy statement of what the path computes, written from the
+paper's definitions (Sec. 3 Eq. 1-2; Sec. 4.2 Eq. 14-18; Sec. 4.3; Alg. 1). It
+shares no code with the HIP library, imports nothing from it, and must never be
+called by it: only tests, the smoke check and the benchmark's CPU-baseline leg
+use it. NumPy's matmul / exp / log are the only library steps; nothing is
+blocked, fused or reordered beyond what the definitions say.
+
+Every function here is pinned by tests that do not go through this module's own
+formulas (closed forms, brute-force enumeration, invariants, finite differences,
+library log-softmax and autograd); none is "parity unpinned". Readings of the
+paper where it is silent (sample std, realised-count constants, first-fit scan,
+weights on the KL term, ...) are listed with each function.
+"""
+from __future__ import annotations
+
+import math
+from typing import Optional
+
+import numpy as np
+
+
+# ----------------------------------------------------------------------------
+# Sec. 3, Eq. 2: group-relative advantages
+# ----------------------------------------------------------------------------
+def group_advantages(rewards, ddof: int = 1, eps: float = 1e-6) -> np.ndarray:
+    """A[k,i] = (r[k,i] - mean_k) / (std_k + eps), one group per row (Eq. 2).
+
+    Reading: the paper says only "std"; ddof selects population (0) or sample (1)
+    and eps is added to the standard deviation so constant groups give A = 0.
+    """
+    r = np.asarray(rewards, dtype=np.float64)
+    Q, G = r.shape
+    if G - ddof <= 0:
+        raise ValueError("G - ddof must be positive")
+    A = np.empty_like(r)
+    for k in range(Q):
+        mu = sum(float(x) for x in r[k]) / G
+        var = sum((float(x) - mu) ** 2 for x in r[k]) / (G - ddof)
+        sd = math.sqrt(var)
+        for i in range(G):
+            A[k, i] = (float(r[k, i]) - mu) / (sd + eps)
+    return A
+
+
+def completion_candidates(rewards) -> np.ndarray:
+    """Candidate test of Eq. 15: |A_i| <= mean_j |A_j| within a group (inclusive).
+
+    Both sides of the inequality carry the same positive factor 1/(std+eps) and the
+    same 1/G, so it is decided on the scaled integers-friendly form
+        G * |G r_i - S|  <=  sum_j |G r_j - S| ,   S = sum_j r_j ,
+    in fp64, left to right, without fused multiply-add. With binary or small
+    integer rewards every quantity is an exact integer, so ties (balanced groups,
+    constant groups) come out as the real-number inequality says.
+    """
+    r = np.asarray(rewards, dtype=np.float64)
+    Q, G = r.shape
+    cand = np.zeros((Q, G), dtype=bool)
+    for k in range(Q):
+        S = 0.0
+        for i in range(G):
+            S = S + float(r[k, i])
+        e = [abs(float(G) * float(r[k, i]) - S) for i in range(G)]
+        tot = 0.0
+        for i in range(G):
+            tot = tot + e[i]
+        for i in range(G):
+            cand[k, i] = (float(G) * e[i]) <= tot
+    return cand
+
+
+def prompt_candidates(hist, bottom_frac: float = 0.5) -> np.ndarray:
+    """B_t of Eq. 17: the floor(bottom_frac*Q) prompts with the lowest history score.
+
+    Reading: ties are broken by the lower prompt index; for odd Q the count is
+    rounded down.
+    """
+    h = np.asarray(hist, dtype=np.float32)
+    Q = h.shape[0]
+    n_b = int(math.floor(float(np.float32(bottom_frac)) * Q))
+    idx = sorted(range(Q), key=lambda k: (float(h[k]), k))
+    inB = np.zeros(Q, dtype=bool)
+    for k in idx[:n_b]:
+        inB[k] = True
+    return inB
+
+
+# ----------------------------------------------------------------------------
+# Sec. 4.2: pruning policies (Eq. 14-17), realised masks, rescaling (Eq. 18)
+# ----------------------------------------------------------------------------
+def select(rewards, hist, u_prompt, u_comp, r_q: float, r_o: float,
+           ddof: int = 1, eps: float = 1e-6, bottom_frac: float = 0.5) -> dict:
+    """Advantages, prune masks and importance-rescaling weights for one batch.
+
+    Pruning is the Bernoulli form of Eq. 15 / Eq. 17 with caller-supplied uniforms:
+    a candidate is pruned iff its uniform is < r (float32 comparison). hist=None
+    skips prompt-level pruning (first epoch), u_*=None skips that level.
+    A pruned prompt drops all its completions. Advantages always come from the
+    full group (Alg. 1 computes them before pruning).
+
+    Weights follow Eq. 18 with the realised counts:
+        gamma_q[k]   = (|S^q| / Q) / (1 - P^q[k])
+        gamma_o[k,i] = (|S^o_k| / G) / (1 - P^o[k,i])
+    and coef[k,i] = gamma_q*gamma_o / (|S^q| * |S^o_k|) is the weight of sequence
+    (k,i) in the batch loss (mean over retained prompts of the mean over retained
+    completions), 0 for pruned sequences.
+    """
+    r = np.asarray(rewards, dtype=np.float32)
+    Q, G = r.shape
+    rq = float(np.float32(r_q))
+    ro = float(np.float32(r_o))
+    A = group_advantages(r, ddof, eps)
+    mean_abs = np.array([sum(abs(float(a)) for a in A[k]) / G for k in range(Q)])
+    cand = completion_candidates(r)
+    inB = prompt_candidates(hist, bottom_frac) if hist is not None else np.zeros(Q, dtype=bool)
+    if u_prompt is None:
+        inB_eff = np.zeros(Q, dtype=bool)
+    else:
+        inB_eff = inB
+    Pq = np.where(inB_eff, rq, 0.0)
+    Po = np.where(cand, ro, 0.0) if u_comp is not None else np.zeros((Q, G))
+
+    keep_prompt = np.ones(Q, dtype=np.uint8)
+    if u_prompt is not None:
+        up = np.asarray(u_prompt, dtype=np.float32)
+        for k in range(Q):
+            if inB_eff[k] and up[k] < np.float32(r_q):
+                keep_prompt[k] = 0
+    keep_comp = np.zeros((Q, G), dtype=np.uint8)
+    uc = None if u_comp is None else np.asarray(u_comp, dtype=np.float32).reshape(Q, G)
+    for k in range(Q):
+        for i in range(G):
+            pruned = (uc is not None) and bool(cand[k, i]) and (uc[k, i] < np.float32(r_o))
+            keep_comp[k, i] = 1 if (keep_prompt[k] and not pruned) else 0
+
+    n_q = int(keep_prompt.sum())
+    n_o = keep_comp.sum(axis=1).astype(np.int64)
+    gamma_q = np.zeros(Q)
+    gamma_o = np.zeros((Q, G))
+    coef = np.zeros((Q, G))
+    for k in range(Q):
+        if not keep_prompt[k]:
+            continue
+        gamma_q[k] = (n_q / Q) / (1.0 - Pq[k])
+        for i in range(G):
+            if keep_comp[k, i]:
+                gamma_o[k, i] = (int(n_o[k]) / G) / (1.0 - Po[k, i])
+                coef[k, i] = gamma_q[k] * gamma_o[k, i] / (n_q * int(n_o[k]))
+    return dict(adv=A, mean_abs_adv=mean_abs, cand=cand, in_bottom=inB_eff,
+                keep_prompt=keep_prompt, keep_comp=keep_comp,
+                gamma_q=gamma_q, gamma_o=gamma_o, coef=coef,
+                counts=np.concatenate([[n_q], n_o]).astype(np.int32),
+                P_q=Pq, P_o=Po)
+
+
+# ----------------------------------------------------------------------------
+# Sec. 4.3: Dense Prompt Packing (window-based greedy selection)
+# ----------------------------------------------------------------------------
+def pack(prompt_len, comp_len, keep, capacity: int, n_win: int) -> dict:
+    """Window-based greedy packing of the kept sequences into rows of `capacity` tokens.
+
+    Items are the kept sequences in index order, length = prompt + completion.
+    A pool holds up to n_win items in arrival order and is refilled from the stream
+    after every placement. For each row, the pool is scanned from its oldest item
+    to its newest (items fetched during the scan included) and every item that
+    still fits the remaining space is placed (reading: first-fit in arrival order;
+    the paper only says "greedily select samples that fit").
+
+    Returns order (original item indices in packed order), row_ptr (row boundaries
+    in sequences), cu_seqlens (token offsets of the packed sequences), loss_cu
+    (offsets into the compact loss-token index) and loss_pos (packed positions
+    whose hidden state predicts a completion token: for a sequence starting at c
+    with prompt P and completion C these are c+P-1 ... c+P+C-2).
+    """
+    pl = np.asarray(prompt_len, dtype=np.int64)
+    cl = np.asarray(comp_len, dtype=np.int64)
+    n_all = pl.shape[0]
+    kept = [j for j in range(n_all) if keep is None or keep[j]]
+    for j in kept:
+        if pl[j] < 1 or cl[j] < 1 or pl[j] + cl[j] > capacity:
+            raise ValueError("item %d does not fit a row or has an empty part" % j)
+    if n_win < 1:
+        raise ValueError("n_win must be >= 1")
+    n = len(kept)
+    stream = list(kept)
+    pool = stream[:min(n_win, n)]
+    nxt = len(pool)
+    order, row_ptr = [], [0]
+    while pool:
+        rem = capacity
+        pos = 0
+        while pos < len(pool):
+            j = pool[pos]
+            ell = int(pl[j] + cl[j])
+            if ell <= rem:
+                order.append(j)
+                rem -= ell
+                del pool[pos]
+                if nxt < n:
+                    pool.append(stream[nxt])
+                    nxt += 1
+            else:
+                pos += 1
+        row_ptr.append(len(order))
+    cu = [0]
+    lcu = [0]
+    loss_pos = []
+    for j in order:
+        c0 = cu[-1]
+        P, C = int(pl[j]), int(cl[j])
+        loss_pos.extend(range(c0 + P - 1, c0 + P + C - 1))
+        cu.append(c0 + P + C)
+        lcu.append(lcu[-1] + C)
+    return dict(order=np.array(order, dtype=np.int32), row_ptr=np.array(row_ptr, dtype=np.int32),
+                cu_seqlens=np.array(cu, dtype=np.int32), loss_cu=np.array(lcu, dtype=np.int32),
+                loss_pos=np.array(loss_pos, dtype=np.int32),
+                n_rows=len(row_ptr) - 1, T=cu[-1], N=lcu[-1], S=n)
+
+
+# ----------------------------------------------------------------------------
+# pi_theta(o_t | q, o_<t): LM-head projection, log-softmax, target gather
+# ----------------------------------------------------------------------------
+def _targets(ids, loss_pos, N):
+    ids = np.asarray(ids)
+    if loss_pos is None:
+        return np.arange(N), ids[:N].astype(np.int64)
+    lp = np.asarray(loss_pos, dtype=np.int64)
+    return lp, ids[lp + 1].astype(np.int64)
+
+
+def token_logprob(H, W, ids, loss_pos):
+    """logp[n] = z[n, y_n] - log sum_v exp z[n, v],  z = H[loss_pos] W^T  (no bias, T=1).
+
+    y_n = ids[loss_pos[n] + 1]: the hidden state at a position predicts the next
+    token. loss_pos=None means rows of H are the loss rows and ids[n] the targets.
+    """
+    H = np.asarray(H, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    N = H.shape[0] if loss_pos is None else len(loss_pos)
+    rows, y = _targets(ids, loss_pos, N)
+    Z = H[rows] @ W.T
+    m = Z.max(axis=1)
+    lse = m + np.log(np.exp(Z - m[:, None]).sum(axis=1))
+    logp = Z[np.arange(N), y] - lse
+    return logp, lse
+
+
+# ----------------------------------------------------------------------------
+# Sec. 3 Eq. 1 with the rescaling of Eq. 18: loss and gradients
+# ----------------------------------------------------------------------------
+def token_terms(logp, logp_old, logp_ref, A, clip_lo: float, clip_hi: float, beta: float):
+    """Per-token loss and its derivative w.r.t. logp (Eq. 1, one token).
+
+    rho = pi/pi_old; surrogate = min(rho*A, clip(rho, 1-lo, 1+hi)*A);
+    KL = rho_hat - log rho_hat - 1 with rho_hat = pi_ref/pi;  loss = -surrogate + beta*KL.
+    The derivative of the min/clip takes the unclipped branch on ties.
+    """
+    logp = np.asarray(logp, dtype=np.float64)
+    d_old = logp - np.asarray(logp_old, dtype=np.float64)
+    d_ref = np.asarray(logp_ref, dtype=np.float64) - logp
+    rho = np.exp(d_old)
+    lo, hi = 1.0 - clip_lo, 1.0 + clip_hi
+    unclipped = rho * A
+    clipped = np.clip(rho, lo, hi) * A
+    surrogate = np.minimum(unclipped, clipped)
+    rho_hat = np.exp(d_ref)
+    kl = rho_hat - d_ref - 1.0
+    ell = -surrogate + beta * kl
+    clipped_away = ((A > 0) & (rho > hi)) | ((A < 0) & (rho < lo))
+    g = np.where(clipped_away, 0.0, -A * rho) + beta * (1.0 - rho_hat)
+    return ell, g, kl, clipped_away
+
+
+def loss_fwd_bwd(H, W, ids, loss_pos, loss_cu, seq_adv, seq_coef, logp_old, logp_ref,
+                 clip_lo: float = 0.2, clip_hi: float = 0.2, beta: float = 0.04) -> dict:
+    """Loss L = sum_s coef_s * (1/C_s) sum_{n in s} loss_n  (= -J of Eq. 1, reweighted) and
+    its gradients w.r.t. H (rows at loss_pos; all other rows zero) and W.
+
+    Reading: the rescaling weight multiplies the whole per-sequence term (surrogate
+    and KL), and |o_i| is the number of completion tokens C_s.
+    """
+    H = np.asarray(H, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    loss_cu = np.asarray(loss_cu, dtype=np.int64)
+    S = len(loss_cu) - 1
+    N = int(loss_cu[-1])
+    rows, y = _targets(ids, loss_pos, N)
+    Hn = H[rows]
+    Z = Hn @ W.T
+    m = Z.max(axis=1)
+    lse = m + np.log(np.exp(Z - m[:, None]).sum(axis=1))
+    logp = Z[np.arange(N), y] - lse
+
+    A_tok = np.empty(N)
+    w_tok = np.empty(N)
+    for s in range(S):
+        a, b = int(loss_cu[s]), int(loss_cu[s + 1])
+        A_tok[a:b] = float(seq_adv[s])
+        w_tok[a:b] = float(seq_coef[s]) / (b - a)
+    ell, g, kl, clipped = token_terms(logp, logp_old, logp_ref, A_tok, clip_lo, clip_hi, beta)
+    seq_loss = np.array([ell[int(loss_cu[s]):int(loss_cu[s + 1])].mean() for s in range(S)]) \
+        if S else np.zeros(0)
+    loss = float(np.sum(np.asarray(seq_coef, dtype=np.float64) * seq_loss))
+
+    c = w_tok * g                                  # dL/dlogp[n]
+    dZ = -np.exp(Z - lse[:, None]) * c[:, None]    # -c_n p[n,v]
+    dZ[np.arange(N), y] += c                       # + c_n 1[v = y_n]
+    dH = np.zeros_like(H)
+    np.add.at(dH, rows, dZ @ W)
+    dW = dZ.T @ Hn
+    return dict(loss=loss, logp=logp, lse=lse, seq_loss=seq_loss, dH=dH, dW=dW, c=c,
+                mean_kl=float(kl.mean()) if N else 0.0,
+                clip_frac=float(clipped.mean()) if N else 0.0)

@@ -1,0 +1,487 @@
+"""Pins for the CPU oracle: every check here compares it with something other than
+its own formulas -- values the paper prints, closed forms, exact rational
+arithmetic, brute-force enumeration, independent re-implementations of textbook
+routines, library log-softmax / autograd, finite differences."""
+import itertools
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import dppo_oracle as O
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ------------------------------------------------------------------ advantages
+@pytest.mark.parametrize("ddof", [0, 1])
+def test_advantages_sum_to_zero_and_unit_scale(ddof):
+    rng = np.random.default_rng(1)
+    r = rng.normal(size=(7, 9))
+    A = O.group_advantages(r, ddof=ddof, eps=0.0)
+    assert np.abs(A.sum(axis=1)).max() < 1e-12 * 9
+    # (Eq. 2) with eps = 0 the normalised values have sum of squares G - ddof
+    assert np.allclose((A ** 2).sum(axis=1), 9 - ddof, rtol=1e-12)
+    # against the library definition
+    ref = (r - r.mean(axis=1, keepdims=True)) / r.std(axis=1, ddof=ddof, keepdims=True)
+    assert np.allclose(A, ref, rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("G,ddof", [(4, 1), (8, 1), (8, 0), (16, 1), (5, 0)])
+def test_binary_reward_closed_form(G, ddof):
+    # k ones of G: p = k/G, sigma = sqrt(p(1-p) G/(G-ddof)), A_one = (1-p)/sigma, A_zero = -p/sigma,
+    # mean|A| = 2p(1-p)/sigma, so the candidates are the majority class (all if balanced/constant).
+    for k in range(G + 1):
+        r = np.zeros((1, G), dtype=np.float32)
+        r[0, :k] = 1.0
+        A = O.group_advantages(r, ddof=ddof, eps=0.0) if 0 < k < G else O.group_advantages(r, ddof=ddof)
+        cand = O.completion_candidates(r)[0]
+        if k in (0, G):
+            assert np.all(A == 0.0) and cand.all()
+            continue
+        p = k / G
+        sigma = math.sqrt(p * (1 - p) * G / (G - ddof))
+        assert np.allclose(A[0, :k], (1 - p) / sigma, rtol=1e-12)
+        assert np.allclose(A[0, k:], -p / sigma, rtol=1e-12)
+        sel = O.select(r, None, None, None, 0.0, 0.0, ddof=ddof, eps=0.0)
+        assert math.isclose(sel["mean_abs_adv"][0], 2 * p * (1 - p) / sigma, rel_tol=1e-12)
+        if 2 * k == G:
+            assert cand.all()
+        elif 2 * k > G:
+            assert cand[:k].all() and not cand[k:].any()
+        else:
+            assert cand[k:].all() and not cand[:k].any()
+
+
+def test_candidates_match_exact_rational_inequality():
+    # Eq. 15 decided in exact arithmetic on integer rewards: |r_i - mu| <= mean_j |r_j - mu|
+    rng = np.random.default_rng(7)
+    for _ in range(300):
+        G = int(rng.integers(2, 17))
+        r = rng.integers(0, 4, size=G)
+        mu = Fraction(int(r.sum()), G)
+        dev = [abs(Fraction(int(x)) - mu) for x in r]
+        thr = sum(dev, Fraction(0)) / G
+        want = np.array([d <= thr for d in dev])
+        got = O.completion_candidates(r[None, :].astype(np.float32))[0]
+        assert np.array_equal(got, want), (r, got, want)
+
+
+def test_candidates_agree_with_float_advantages_away_from_ties():
+    rng = np.random.default_rng(3)
+    r = rng.normal(size=(200, 8)).astype(np.float32)
+    A = O.group_advantages(r)
+    thr = np.abs(A).mean(axis=1, keepdims=True)
+    margin = np.abs(np.abs(A) - thr)
+    cand = O.completion_candidates(r)
+    clear = margin > 1e-6
+    assert np.array_equal(cand[clear], (np.abs(A) <= thr)[clear])
+
+
+# ---------------------------------------------------------- prompt candidates
+def test_prompt_candidates_rank_and_ties():
+    hist = np.array([0.5, 0.0, 0.5, 0.0, 0.9, 0.0, 0.1], dtype=np.float32)
+    inB = O.prompt_candidates(hist, 0.5)          # floor(3.5) = 3 lowest: the three zeros
+    assert inB.tolist() == [False, True, False, True, False, True, False]
+    hist = np.zeros(6, dtype=np.float32)          # all tied: lowest indices first
+    assert O.prompt_candidates(hist, 0.5).tolist() == [True, True, True, False, False, False]
+    rng = np.random.default_rng(0)
+    h = rng.random(31).astype(np.float32)
+    inB = O.prompt_candidates(h, 0.5)
+    assert inB.sum() == 15 and h[inB].max() <= h[~inB].min()
+
+
+# -------------------------------------------------------------------- weights
+def test_no_pruning_recovers_plain_grpo_weights():
+    rng = np.random.default_rng(2)
+    r = (rng.random((6, 5)) < 0.5).astype(np.float32)
+    for kw in (dict(hist=None, u_prompt=None, u_comp=None, r_q=0.5, r_o=0.5),
+               dict(hist=rng.random(6), u_prompt=rng.random(6), u_comp=rng.random((6, 5)), r_q=0.0, r_o=0.0)):
+        s = O.select(r, kw["hist"], kw["u_prompt"], kw["u_comp"], kw["r_q"], kw["r_o"])
+        assert s["keep_prompt"].all() and s["keep_comp"].all()
+        assert np.all(s["gamma_q"] == 1.0) and np.all(s["gamma_o"] == 1.0)
+        assert np.allclose(s["coef"], 1.0 / 30, rtol=1e-15)
+
+
+def _golden_factor_rows():
+    rows = []
+    with open(os.path.join(GOLDEN, "thm_d1_variance_factor.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                b, r, rel, v = line.split()
+                rows.append((float(b), float(r), rel, float(v)))
+    return rows
+
+
+@pytest.mark.parametrize("beta,r_q,rel,value", _golden_factor_rows())
+def test_prompt_weights_reproduce_printed_variance_factor(beta, r_q, rel, value):
+    # 200 prompts, bottom half candidates, exactly r_q*100 of them pruned (uniforms chosen so):
+    # the mean of gamma_q^2 over retained prompts is the paper's factor (App. D.3).
+    Q, G = 200, 2
+    hist = np.arange(Q, dtype=np.float32)
+    n_prune = int(round(r_q * beta * Q))
+    u_prompt = np.ones(Q, dtype=np.float32) * 0.999
+    u_prompt[:n_prune] = 0.0
+    rewards = np.zeros((Q, G), dtype=np.float32)
+    s = O.select(rewards, hist, u_prompt, None, r_q, 0.0, bottom_frac=beta)
+    kept = s["keep_prompt"].astype(bool)
+    assert kept.sum() == Q - n_prune
+    got = float((s["gamma_q"][kept] ** 2).mean())
+    closed = (1 - beta * r_q) * (1 - (1 - beta) * r_q) / (1 - r_q)
+    assert math.isclose(got, closed, rel_tol=1e-6)    # r_q goes through float32
+    if rel == "le":
+        assert got <= value and got > value - 0.02
+    else:
+        assert abs(got - value) < 5e-4
+
+
+def _enumerate_masks(rewards, hist, r_q, r_o, bottom_frac=0.5):
+    """All joint prune masks with their probabilities, realised through the uniforms."""
+    Q, G = rewards.shape
+    inB = O.prompt_candidates(hist, bottom_frac) if hist is not None else np.zeros(Q, bool)
+    cand = O.completion_candidates(rewards)
+    pb = [k for k in range(Q) if inB[k]]
+    cb = [(k, i) for k in range(Q) for i in range(G) if cand[k, i]]
+    for bits_q in itertools.product([0, 1], repeat=len(pb)):
+        for bits_o in itertools.product([0, 1], repeat=len(cb)):
+            up = np.full(Q, 0.999, dtype=np.float32)
+            uc = np.full((Q, G), 0.999, dtype=np.float32)
+            prob = 1.0
+            for b, k in zip(bits_q, pb):
+                if b:
+                    up[k] = 0.0
+                prob *= r_q if b else (1 - r_q)
+            for b, (k, i) in zip(bits_o, cb):
+                if b:
+                    uc[k, i] = 0.0
+                prob *= r_o if b else (1 - r_o)
+            yield prob, up, uc
+
+
+@pytest.mark.parametrize("Q,G,seed", [(2, 3, 0), (3, 3, 1), (2, 4, 2), (3, 2, 3)])
+def test_expected_weight_is_unpruned_weight(Q, G, seed):
+    # Eq. 9, 12, 13 in the discrete setting: averaging coef over every prune mask,
+    # weighted by its probability, gives each completion the plain GRPO weight 1/(QG).
+    rng = np.random.default_rng(seed)
+    rewards = (rng.random((Q, G)) < 0.5).astype(np.float32)
+    hist = rng.random(Q).astype(np.float32)
+    r_q, r_o = 0.5, 0.25
+    acc = np.zeros((Q, G))
+    ptot = 0.0
+    for prob, up, uc in _enumerate_masks(rewards, hist, r_q, r_o):
+        acc += prob * O.select(rewards, hist, up, uc, r_q, r_o)["coef"]
+        ptot += prob
+    assert math.isclose(ptot, 1.0, rel_tol=1e-12)
+    assert np.allclose(acc, 1.0 / (Q * G), rtol=1e-12)
+
+
+def test_weights_equal_horvitz_thompson_form():
+    rng = np.random.default_rng(5)
+    Q, G = 10, 6
+    rewards = (rng.random((Q, G)) < 0.4).astype(np.float32)
+    s = O.select(rewards, rng.random(Q), rng.random(Q), rng.random((Q, G)), 0.5, 0.5)
+    kept = s["keep_comp"].astype(bool)
+    ht = 1.0 / (Q * G * (1 - s["P_q"][:, None]) * (1 - s["P_o"]))
+    assert np.allclose(s["coef"][kept], ht[kept], rtol=1e-12)
+    assert np.all(s["coef"][~kept] == 0.0)
+    assert not kept[~s["keep_prompt"].astype(bool)].any()
+    assert s["counts"][0] == s["keep_prompt"].sum()
+    assert np.array_equal(s["counts"][1:], kept.sum(axis=1))
+
+
+# -------------------------------------------------------------------- packing
+def _next_fit(lens, cap):
+    rows, cur, rem = [], [], cap
+    for j, l in enumerate(lens):
+        if l > rem:
+            rows.append(cur)
+            cur, rem = [], cap
+        cur.append(j)
+        rem -= l
+    if cur:
+        rows.append(cur)
+    return rows
+
+
+def _first_fit(lens, cap):
+    rows, rems = [], []
+    for j, l in enumerate(lens):
+        for b in range(len(rows)):
+            if l <= rems[b]:
+                rows[b].append(j)
+                rems[b] -= l
+                break
+        else:
+            rows.append([j])
+            rems.append(cap - l)
+    return rows
+
+
+def _window_restart_scan(lens, cap, n_win):
+    """Second statement of Sec. 4.3: after every placement rescan the pool from its oldest item."""
+    n = len(lens)
+    pool = list(range(min(n_win, n)))
+    nxt = len(pool)
+    rows = []
+    while pool:
+        row, rem = [], cap
+        while True:
+            hit = next((j for j in pool if lens[j] <= rem), None)
+            if hit is None:
+                break
+            row.append(hit)
+            rem -= lens[hit]
+            pool.remove(hit)
+            if nxt < n:
+                pool.append(nxt)
+                nxt += 1
+        rows.append(row)
+    return rows
+
+
+def _rows_of(p):
+    return [p["order"][p["row_ptr"][r]:p["row_ptr"][r + 1]].tolist() for r in range(p["n_rows"])]
+
+
+def test_pack_hand_worked_cases():
+    ones = np.ones(5, dtype=np.int64)
+    p = O.pack(ones, np.array([5, 4, 3, 6, 2]) - 1, None, 10, 2)
+    assert p["order"].tolist() == [0, 1, 2, 3, 4] and p["row_ptr"].tolist() == [0, 2, 4, 5]
+    p = O.pack(ones, np.array([7, 5, 3, 4, 2]) - 1, None, 10, 3)
+    assert p["order"].tolist() == [0, 2, 1, 3, 4] and p["row_ptr"].tolist() == [0, 2, 4, 5]
+    # offsets: prompt 2 + completion 3 starting at 0, then prompt 1 + completion 2
+    p = O.pack(np.array([2, 1]), np.array([3, 2]), None, 16, 4)
+    assert p["cu_seqlens"].tolist() == [0, 5, 8] and p["loss_cu"].tolist() == [0, 3, 5]
+    assert p["loss_pos"].tolist() == [1, 2, 3, 5, 6]
+
+
+def test_pack_invariants_and_reductions():
+    rng = np.random.default_rng(11)
+    for trial in range(200):
+        n = int(rng.integers(1, 40))
+        cap = int(rng.integers(8, 64))
+        pl = rng.integers(1, cap // 2 + 1, size=n)
+        cl = rng.integers(1, cap - pl + 1)
+        lens = (pl + cl).tolist()
+        for n_win in (1, 2, 5, n, n + 7):
+            p = O.pack(pl, cl, None, cap, n_win)
+            rows = _rows_of(p)
+            assert sorted(p["order"].tolist()) == list(range(n))
+            assert all(sum(lens[j] for j in row) <= cap for row in rows)
+            assert p["T"] == sum(lens) == p["cu_seqlens"][-1]
+            assert p["N"] == int(cl.sum()) == p["loss_cu"][-1] == len(p["loss_pos"])
+            assert p["n_rows"] >= math.ceil(sum(lens) / cap)
+            assert rows == _window_restart_scan(lens, cap, n_win)
+            if n_win == 1:
+                assert rows == _next_fit(lens, cap)
+            if n_win >= n:
+                assert rows == _first_fit(lens, cap)
+            # loss positions: inside their sequence, and the next position is a completion token
+            for s, j in enumerate(p["order"]):
+                a, b = p["loss_cu"][s], p["loss_cu"][s + 1]
+                lp = p["loss_pos"][a:b]
+                assert b - a == cl[j]
+                assert lp[0] == p["cu_seqlens"][s] + pl[j] - 1
+                assert lp[-1] == p["cu_seqlens"][s + 1] - 2
+                assert np.all(np.diff(lp) == 1)
+
+
+def test_pack_equal_lengths_and_keep_mask():
+    p = O.pack(np.full(23, 3), np.full(23, 4), None, 30, 6)
+    assert p["n_rows"] == math.ceil(23 / (30 // 7))
+    keep = np.array([1, 0, 1, 1, 0, 1], dtype=np.uint8)
+    pl = np.array([2, 9, 3, 4, 9, 5])
+    cl = np.array([2, 9, 2, 2, 9, 2])
+    p = O.pack(pl, cl, keep, 10, 2)
+    q = O.pack(pl[keep == 1], cl[keep == 1], None, 10, 2)
+    assert p["order"].tolist() == np.flatnonzero(keep)[q["order"]].tolist()
+    assert p["cu_seqlens"].tolist() == q["cu_seqlens"].tolist()
+    assert p["S"] == 4
+    with pytest.raises(ValueError):
+        O.pack(np.array([6]), np.array([6]), None, 10, 2)
+
+
+# ------------------------------------------------------------------ log-probs
+def _tiny_head(seed, N=11, D=8, V=16):
+    rng = np.random.default_rng(seed)
+    H = rng.normal(size=(N + 3, D))
+    W = rng.normal(size=(V, D)) * 0.5
+    ids = rng.integers(0, V, size=N + 3)
+    loss_pos = np.array([0, 1, 2, 4, 5, 6, 7, 9, 10, 11, 12][:N]) if N <= 11 else np.arange(N)
+    return H, W, ids, loss_pos
+
+
+def test_logprob_special_cases():
+    H, W, ids, lp = _tiny_head(0)
+    V = W.shape[0]
+    logp, lse = O.token_logprob(H, np.zeros_like(W), ids, lp)
+    assert np.allclose(logp, -math.log(V), rtol=1e-14) and np.allclose(lse, math.log(V))
+    logp, _ = O.token_logprob(H, np.tile(W[:1], (V, 1)), ids, lp)
+    assert np.allclose(logp, -math.log(V), rtol=1e-12)
+    # a constant added to every logit of a row does not change log-probs
+    base, _ = O.token_logprob(H, W, ids, lp)
+    H1 = np.concatenate([H, np.ones((H.shape[0], 1))], axis=1)
+    W1 = np.concatenate([W, np.full((V, 1), 3.7)], axis=1)
+    shifted, lse1 = O.token_logprob(H1, W1, ids, lp)
+    assert np.allclose(base, shifted, rtol=1e-12, atol=1e-12)
+    # probabilities of a row sum to one
+    Z = H1[lp] @ W1.T
+    assert np.allclose(np.exp(Z - lse1[:, None]).sum(axis=1), 1.0, rtol=1e-12)
+
+
+def test_logprob_matches_library_log_softmax():
+    import torch
+    H, W, ids, lp = _tiny_head(1)
+    logp, lse = O.token_logprob(H, W, ids, lp)
+    Ht, Wt = torch.tensor(H), torch.tensor(W)
+    lsm = torch.log_softmax(Ht[torch.tensor(lp)] @ Wt.T, dim=-1)
+    y = torch.tensor(ids[lp + 1]).long()
+    want = lsm.gather(1, y[:, None])[:, 0].numpy()
+    assert np.allclose(logp, want, rtol=1e-12, atol=1e-12)
+    # identity indexing form
+    logp2, _ = O.token_logprob(H[lp], W, ids[lp + 1], None)
+    assert np.allclose(logp, logp2, rtol=0, atol=0)
+
+
+# ------------------------------------------------------------ loss and grads
+def _loss_case(seed, clip_noise=0.3):
+    rng = np.random.default_rng(seed)
+    pl = np.array([2, 3, 1, 2])
+    cl = np.array([3, 1, 4, 2])
+    p = O.pack(pl, cl, None, 12, 2)
+    T, N = p["T"], p["N"]
+    D, V = 6, 13
+    H = rng.normal(size=(T, D))
+    W = rng.normal(size=(V, D)) * 0.7
+    ids = rng.integers(0, V, size=T)
+    base, _ = O.token_logprob(H, W, ids, p["loss_pos"])
+    old = base + rng.normal(0, clip_noise, size=N)
+    ref = base + rng.normal(0, 0.2, size=N)
+    adv = np.array([1.3, -0.7, 0.4, -1.1])
+    coef = np.array([0.1, 0.4, 0.25, 0.3])
+    return p, H, W, ids, old, ref, adv, coef
+
+
+def test_coincident_policies_give_unit_ratio_zero_kl():
+    p, H, W, ids, _, _, adv, coef = _loss_case(0)
+    base, _ = O.token_logprob(H, W, ids, p["loss_pos"])
+    out = O.loss_fwd_bwd(H, W, ids, p["loss_pos"], p["loss_cu"], adv, coef, base, base)
+    assert np.allclose(out["seq_loss"], -adv, rtol=1e-12)
+    assert math.isclose(out["loss"], -float(coef @ adv), rel_tol=1e-12)
+    assert out["mean_kl"] == 0.0 and out["clip_frac"] == 0.0
+    # plain GRPO weights and full groups: the loss vanishes because advantages sum to zero
+    r = np.array([[1, 0, 0, 1], [0, 0, 1, 0]], dtype=np.float32)
+    s = O.select(r, None, None, None, 0.0, 0.0)
+    rng = np.random.default_rng(4)
+    pl, cl = np.repeat([2, 3], 4), rng.integers(1, 5, size=8)
+    pk = O.pack(pl, cl, None, 16, 3)
+    Hh = rng.normal(size=(pk["T"], 5)); Ww = rng.normal(size=(9, 5)); ii = rng.integers(0, 9, pk["T"])
+    b, _ = O.token_logprob(Hh, Ww, ii, pk["loss_pos"])
+    out = O.loss_fwd_bwd(Hh, Ww, ii, pk["loss_pos"], pk["loss_cu"],
+                         s["adv"].reshape(-1)[pk["order"]], s["coef"].reshape(-1)[pk["order"]], b, b)
+    assert abs(out["loss"]) < 1e-12
+
+
+def test_loss_and_grads_match_autograd():
+    import torch
+    p, H, W, ids, old, ref, adv, coef = _loss_case(1)
+    out = O.loss_fwd_bwd(H, W, ids, p["loss_pos"], p["loss_cu"], adv, coef, old, ref, 0.2, 0.25, 0.04)
+    assert out["clip_frac"] > 0.0          # the case does exercise clipping
+    Ht = torch.tensor(H, requires_grad=True)
+    Wt = torch.tensor(W, requires_grad=True)
+    lp = torch.tensor(p["loss_pos"]).long()
+    y = torch.tensor(ids[p["loss_pos"] + 1]).long()
+    logp = torch.log_softmax(Ht[lp] @ Wt.T, dim=-1).gather(1, y[:, None])[:, 0]
+    total = torch.zeros((), dtype=torch.float64)
+    for s in range(4):
+        a, b = int(p["loss_cu"][s]), int(p["loss_cu"][s + 1])
+        rho = torch.exp(logp[a:b] - torch.tensor(old[a:b]))
+        sur = torch.minimum(rho * adv[s], torch.clamp(rho, 0.8, 1.25) * adv[s])
+        rh = torch.exp(torch.tensor(ref[a:b]) - logp[a:b])
+        kl = rh - torch.log(rh) - 1
+        total = total + coef[s] * (-(sur) + 0.04 * kl).mean()
+    total.backward()
+    assert math.isclose(out["loss"], float(total.detach()), rel_tol=1e-12)
+    assert np.allclose(out["dH"], Ht.grad.numpy(), rtol=1e-10, atol=1e-14)
+    assert np.allclose(out["dW"], Wt.grad.numpy(), rtol=1e-10, atol=1e-14)
+
+
+def test_gradient_finite_differences_and_invariants():
+    p, H, W, ids, old, ref, adv, coef = _loss_case(2, clip_noise=0.05)
+    f = lambda Hx, Wx: O.loss_fwd_bwd(Hx, Wx, ids, p["loss_pos"], p["loss_cu"], adv, coef, old, ref)
+    out = f(H, W)
+    rng = np.random.default_rng(9)
+    h = 1e-6
+    for _ in range(12):
+        t, d = int(rng.integers(H.shape[0])), int(rng.integers(H.shape[1]))
+        Hp, Hm = H.copy(), H.copy(); Hp[t, d] += h; Hm[t, d] -= h
+        fd = (f(Hp, W)["loss"] - f(Hm, W)["loss"]) / (2 * h)
+        assert abs(fd - out["dH"][t, d]) <= 1e-6 * max(1.0, abs(fd)) + 1e-9
+        v, d = int(rng.integers(W.shape[0])), int(rng.integers(W.shape[1]))
+        Wp, Wm = W.copy(), W.copy(); Wp[v, d] += h; Wm[v, d] -= h
+        fd = (f(H, Wp)["loss"] - f(H, Wm)["loss"]) / (2 * h)
+        assert abs(fd - out["dW"][v, d]) <= 1e-6 * max(1.0, abs(fd)) + 1e-9
+    # softmax gradients sum to zero over the vocabulary
+    assert np.abs(out["dW"].sum(axis=0)).max() < 1e-13
+    # rows that predict nothing get no gradient
+    mask = np.ones(H.shape[0], bool); mask[p["loss_pos"]] = False
+    assert np.all(out["dH"][mask] == 0.0) and np.abs(out["dH"][~mask]).min() > 0
+    # identical vocabulary rows: log-probs do not depend on H
+    Wc = np.tile(W[:1], (W.shape[0], 1))
+    assert np.abs(f(H, Wc)["dH"]).max() < 1e-13
+
+
+def test_expected_loss_and_gradients_are_unbiased_over_all_masks():
+    # Eq. 13 for the full Eq. 1 loss: sum over prune masks of P(mask) * {L, dH, dW}(mask)
+    # equals the unpruned GRPO values; each mask runs select -> pack -> loss from scratch.
+    rng = np.random.default_rng(21)
+    Q, G, D, V = 2, 3, 5, 9
+    rewards = np.array([[1, 1, 1], [0, 1, 0]], dtype=np.float32)   # a constant group can be pruned whole
+    hist = np.array([0.3, 0.1], dtype=np.float32)
+    pl = np.repeat(rng.integers(1, 4, size=Q), G)
+    cl = rng.integers(1, 5, size=Q * G)
+    seqH = [rng.normal(size=(pl[j] + cl[j], D)) for j in range(Q * G)]
+    seqI = [rng.integers(0, V, size=pl[j] + cl[j]) for j in range(Q * G)]
+    W = rng.normal(size=(V, D)) * 0.6
+    seq_old = [rng.normal(0, 0.1, size=cl[j]) for j in range(Q * G)]
+    seq_ref = [rng.normal(0, 0.1, size=cl[j]) for j in range(Q * G)]
+    r_q, r_o = 0.5, 0.375          # exactly representable in float32
+
+    def run(up, uc, rq, ro):
+        s = O.select(rewards, hist, up, uc, rq, ro)
+        keep = s["keep_comp"].reshape(-1)
+        dHs = [np.zeros_like(h) for h in seqH]
+        if keep.sum() == 0:
+            return 0.0, dHs, np.zeros_like(W)
+        pk = O.pack(pl, cl, keep, 16, 2)
+        od = pk["order"]
+        H = np.concatenate([seqH[j] for j in od]); ids = np.concatenate([seqI[j] for j in od])
+        base, _ = O.token_logprob(H, W, ids, pk["loss_pos"])
+        old = base + np.concatenate([seq_old[j] for j in od])
+        ref = base + np.concatenate([seq_ref[j] for j in od])
+        out = O.loss_fwd_bwd(H, W, ids, pk["loss_pos"], pk["loss_cu"],
+                             s["adv"].reshape(-1)[od], s["coef"].reshape(-1)[od], old, ref)
+        for si, j in enumerate(od):
+            dHs[j] = out["dH"][pk["cu_seqlens"][si]:pk["cu_seqlens"][si + 1]]
+        return out["loss"], dHs, out["dW"]
+
+    L0, dH0, dW0 = run(None, None, 0.0, 0.0)
+    EL, EdH, EdW = 0.0, [np.zeros_like(h) for h in seqH], np.zeros_like(W)
+    n_masks = 0
+    saw_empty_group = False
+    for prob, up, uc in _enumerate_masks(rewards, hist, r_q, r_o):
+        L, dHs, dW = run(up, uc, r_q, r_o)
+        EL += prob * L
+        EdW += prob * dW
+        for j in range(Q * G):
+            EdH[j] += prob * dHs[j]
+        n_masks += 1
+        s = O.select(rewards, hist, up, uc, r_q, r_o)
+        saw_empty_group |= bool((s["counts"][1:][s["keep_prompt"] == 1] == 0).any())
+    assert n_masks >= 32 and saw_empty_group
+    assert math.isclose(EL, L0, rel_tol=1e-10)
+    assert np.allclose(EdW, dW0, rtol=1e-9, atol=1e-13)
+    for j in range(Q * G):
+        assert np.allclose(EdH[j], dH0[j], rtol=1e-9, atol=1e-13)
