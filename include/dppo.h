@@ -1,0 +1,186 @@
+/*
+ * dppo.h -- C ABI of the MI355X (gfx950) library for the DPPO policy-loss hot path:
+ * selection (advantages, prune masks, importance-rescaling weights), dense packing,
+ * fused LM-head token log-probabilities, and the reweighted GRPO loss forward+backward.
+ *
+ * Conventions that hold for every call unless an argument says otherwise
+ *   - every array pointer is a DEVICE pointer owned by the caller; the library never
+ *     allocates or frees device memory (scratch is the caller's `ws`);
+ *   - parameter structs and the returned status live on the host;
+ *   - calls are asynchronous on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and never synchronise it;
+ *   - arguments that can be checked on the host (NULL pointers, non-positive sizes,
+ *     rates outside [0,1), too small a workspace) are checked before anything is
+ *     launched: the call returns an error status and launches nothing;
+ *   - conditions only the device can see are reported through a device-side status
+ *     word (see dppo_pack) and leave the outputs defined;
+ *   - no C++ exception crosses this boundary.
+ */
+#ifndef DPPO_H_
+#define DPPO_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DPPO_OK = 0,
+    DPPO_ERR_INVALID_ARG = 1, /* NULL pointer, value out of range                      */
+    DPPO_ERR_SHAPE = 2,       /* non-positive or inconsistent sizes                    */
+    DPPO_ERR_CAPACITY = 3,    /* an item longer than the packing window                */
+    DPPO_ERR_WORKSPACE = 4,   /* workspace missing, misaligned or too small            */
+    DPPO_ERR_UNSUPPORTED = 5, /* shape or dtype outside what the kernels are built for */
+    DPPO_ERR_DEVICE = 6       /* a HIP runtime call failed                             */
+} dppo_status;
+
+/* Static description of a status code (never NULL). */
+const char* dppo_status_str(int status);
+/* Detail of the last error raised on the calling thread ("" if none; never NULL). */
+const char* dppo_last_error(void);
+
+/* --------------------------------------------------------------------------------
+ * dppo_select -- Sec. 3 Eq. 2 and Sec. 4.2 Eq. 14-18 of the paper.
+ *
+ * For a batch of Q prompts with G completions each:
+ *   adv[k,i]        group-relative advantage (r - mean_k) / (std_k + adv_eps), from the
+ *                   full group, std with divisor G - std_ddof                     (Eq. 2)
+ *   mean_abs_adv[k] the prompt's threshold / next-epoch history score            (Eq. 14)
+ *   completion candidates: |adv[k,i]| <= mean_abs_adv[k], decided exactly in fp64 on the
+ *                   equivalent form G|G r_i - S| <= sum_j |G r_j - S|            (Eq. 15)
+ *   prompt candidates: the floor(bottom_frac*Q) prompts with the lowest hist[k], ties to
+ *                   the lower index; none if hist or u_prompt is NULL (first epoch)(Eq. 17)
+ *   masks: a candidate prompt is pruned iff u_prompt[k] < r_q, a candidate completion iff
+ *                   u_comp[k,i] < r_o (float32 compares); completions of a pruned prompt
+ *                   are dropped; u_comp NULL = no completion pruning
+ *   gamma_q[k]   = (|S^q|/Q) / (1 - P^q_k),  gamma_o[k,i] = (|S^o_k|/G) / (1 - P^o_{k,i})
+ *                   with the realised retained counts; 0 for pruned entries      (Eq. 18)
+ *   coef[k,i]    = gamma_q gamma_o / (|S^q| |S^o_k|): weight of sequence (k,i) in the batch
+ *                   loss (mean over retained prompts of the mean over retained completions)
+ *   counts[0] = |S^q|, counts[1+k] = |S^o_k| (0 for a pruned prompt)
+ *
+ * Layout: rewards, u_comp, adv, keep_comp, gamma_o, coef are [Q*G] row-major (prompt
+ * major); hist, u_prompt, mean_abs_adv, keep_prompt, gamma_q are [Q]; counts is [1+Q].
+ * Masks are bit-exact functions of the inputs. Requires Q <= 16384, G <= 1024,
+ * G - std_ddof >= 1, r_q and r_o in [0,1), 0 <= bottom_frac <= 1.
+ */
+typedef struct {
+    int32_t Q, G;
+    float r_q, r_o;     /* prune probabilities of candidate prompts / completions */
+    float adv_eps;      /* added to the standard deviation (1e-6 customary)       */
+    int32_t std_ddof;   /* 0 = population, 1 = sample standard deviation          */
+    float bottom_frac;  /* fraction of prompts that are candidates (paper: 0.5)   */
+} dppo_select_params;
+
+int dppo_select(const dppo_select_params* p,
+                const float* rewards, const float* hist /* or NULL */,
+                const float* u_prompt /* or NULL */, const float* u_comp /* or NULL */,
+                float* adv, float* mean_abs_adv,
+                uint8_t* keep_prompt, uint8_t* keep_comp,
+                float* gamma_q, float* gamma_o, float* coef,
+                int32_t* counts, void* stream);
+
+/* --------------------------------------------------------------------------------
+ * dppo_pack -- Sec. 4.3 (Dense Prompt Packing), applied to the retained sequences.
+ *
+ * Items are the n_items sequences in index order, item j having prompt_len[j] +
+ * comp_len[j] tokens; items with keep[j] == 0 are skipped (keep NULL = all kept).
+ * A pool of up to n_win items in arrival order is refilled from the stream after every
+ * placement; for each row of `capacity` tokens the pool is scanned from oldest to newest
+ * (items fetched meanwhile included) and every item that still fits is placed.
+ *
+ * Outputs (all int32):
+ *   order[s]       original index of the s-th packed sequence           [n_items], S valid
+ *   row_ptr[r]     first packed sequence of row r                       [n_items+1], n_rows+1 valid
+ *   cu_seqlens[s]  first token of packed sequence s; [S] = T            [n_items+1]
+ *   loss_cu[s]     first loss token of packed sequence s; [S] = N       [n_items+1]
+ *   loss_pos[n]    packed position whose hidden state predicts the n-th completion token:
+ *                  sequence s contributes cu[s]+P-1 ... cu[s]+P+C-2     [loss_pos_capacity]
+ *   meta[8]        {n_rows, T, N, device_status, S, 0, 0, 0}
+ * device_status: 0 ok; 1 = a kept item has prompt_len < 1, comp_len < 1 or does not fit
+ * `capacity`; 2 = N exceeds loss_pos_capacity; 3 = T does not fit int32. On a non-zero
+ * status n_rows = T = N = S = 0 and no other output is meaningful.
+ * cu_seqlens and loss_cu are also used as scratch while packing.
+ * The result is a bit-exact function of the inputs (one deterministic wavefront).
+ */
+typedef struct {
+    int32_t n_items, capacity, n_win;
+} dppo_pack_params;
+
+int dppo_pack(const dppo_pack_params* p,
+              const int32_t* prompt_len, const int32_t* comp_len, const uint8_t* keep /* or NULL */,
+              int32_t* order, int32_t* row_ptr, int32_t* cu_seqlens, int32_t* loss_cu,
+              int32_t* loss_pos, int64_t loss_pos_capacity, int32_t* meta, void* stream);
+
+/* dst[i] = src[idx[i]], i < n: puts per-item adv / coef into packed order (idx = order). */
+int dppo_gather_f32(int64_t n, const int32_t* idx, const float* src, float* dst, void* stream);
+
+/* --------------------------------------------------------------------------------
+ * LM head: pi_theta(o_t | q, o_<t) of Sec. 3 as log-softmax of H W^T gathered at the
+ * target token, and the loss of Eq. 1 reweighted by Eq. 18, forward and backward.
+ *
+ * H[T,D] row-major hidden states of the packed tokens, W[V,D] row-major vocabulary
+ * matrix (logits z = H W^T, no bias, temperature 1), ids[T] token ids in [0,V).
+ * loss_pos[N] lists the rows of H that predict a completion token; the target of loss
+ * token n is ids[loss_pos[n]+1]. loss_pos NULL means identity: N <= T rows of H are
+ * loss rows and ids[n] is the target of row n.
+ * dtype 0: H, W float32, fp32 arithmetic. dtype 1: H, W bfloat16, bf16 MFMA with fp32
+ * accumulation (needs D % 64 == 0). Statistics (max, sum-exp, log-probs, loss terms) are
+ * fp32; logits are never written out in full (at most one token chunk at a time, in the
+ * workspace).
+ */
+typedef struct {
+    int64_t T, N;
+    int32_t D, V;
+    int32_t dtype; /* 0 = float32, 1 = bfloat16 */
+} dppo_head_shape;
+
+/* Recommended workspace size in bytes (0 if the shape is invalid). Any size of at least
+ * dppo_workspace_min_bytes works: a smaller workspace means smaller token chunks. */
+size_t dppo_workspace_bytes(const dppo_head_shape* shape, int want_backward);
+size_t dppo_workspace_min_bytes(const dppo_head_shape* shape, int want_backward);
+
+/* logp[n] = z[n,y_n] - lse[n], lse[n] = log sum_v exp z[n,v]; lse may be NULL.
+ * ws must be 256-byte aligned. */
+int dppo_token_logprob(const dppo_head_shape* shape,
+                       const void* H, const void* W, const int32_t* ids,
+                       const int32_t* loss_pos /* or NULL */,
+                       float* logp, float* lse /* or NULL */,
+                       void* ws, size_t ws_bytes, void* stream);
+
+/* Loss L = sum_s seq_coef[s] * (1/C_s) * sum_{n in s} l_n over the S packed sequences
+ * (segments loss_cu[s]..loss_cu[s+1] of the loss tokens, C_s their length), with
+ *   rho = exp(logp - logp_old),  l = -min(rho A, clip(rho, 1-clip_lo, 1+clip_hi) A)
+ *   + beta (rho_hat - log rho_hat - 1),  rho_hat = exp(logp_ref - logp),  A = seq_adv[s]
+ * (Eq. 1; the weight multiplies surrogate and KL alike), and its gradients
+ *   dH[T,D] (dtype of H; rows not in loss_pos are zero) and dW[V,D] (float32; added to
+ *   the buffer's contents if accumulate_dW != 0, otherwise overwritten).
+ * Optional outputs: logp[N]; seq_loss[S] (token-mean loss of each sequence);
+ * stats[4] = {mean KL over loss tokens, fraction of tokens whose surrogate gradient is
+ * clipped away, N, 0}. loss is one float on the device.
+ * recompute_logits = 0 keeps one chunk of logits in the workspace as fp16 (needs
+ * |z| < 65504); 1 runs the vocabulary GEMM a second time in the backward instead.
+ */
+typedef struct {
+    float clip_lo, clip_hi;
+    float beta;
+    int32_t accumulate_dW;
+    int32_t recompute_logits;
+} dppo_loss_params;
+
+int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* p, int32_t S,
+                      const void* H, const void* W, const int32_t* ids,
+                      const int32_t* loss_pos /* or NULL */, const int32_t* loss_cu,
+                      const float* seq_adv, const float* seq_coef,
+                      const float* logp_old, const float* logp_ref,
+                      float* loss, float* logp /* or NULL */, float* seq_loss /* or NULL */,
+                      float* stats /* or NULL */,
+                      void* dH, float* dW,
+                      void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DPPO_H_ */

@@ -1,0 +1,344 @@
+// C ABI of the DPPO HIP library: argument validation, workspace planning and the
+// orchestration of the kernels on the caller's stream. No device memory is allocated here.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "dppo_internal.h"
+
+namespace dppo {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int check_launch(const char* what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(DPPO_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+    return DPPO_OK;
+}
+
+namespace {
+
+constexpr int32_t CHUNK_ALIGN = 256;      // token-chunk granularity (= GEMM tile edge)
+constexpr int32_t CHUNK_MAX = 32768;      // largest token chunk
+constexpr size_t REGION_ALIGN = 256;
+
+struct WsPlan {
+    int32_t Vp, n_tiles, n_cp;     // padded vocabulary, row tiles of the vocabulary GEMM, chunk rows
+    int64_t n_chunks;
+    size_t es, zs;                 // element sizes of H/W and of the stored logits / gradient entries
+    size_t fixed_bytes, row_bytes; // bytes independent of / proportional to the chunk size
+    // region offsets
+    size_t o_wt, o_logp, o_ell, o_kl, o_clip, o_seq, o_hc, o_hct, o_part, o_zg, o_gt, o_y, o_zy, o_lse, o_c;
+    size_t total;
+};
+
+int32_t round_up32(int64_t x, int32_t a) { return (int32_t)((x + a - 1) / a * a); }
+
+// Lays the workspace out for chunk size n_cp (multiple of CHUNK_ALIGN).
+void layout(const dppo_head_shape& s, bool bwd, int32_t n_cp, WsPlan& p) {
+    p.es = s.dtype == 1 ? 2 : 4;
+    p.zs = p.es;
+    p.Vp = round_up32(s.V, 64);
+    p.n_tiles = s.dtype == 1 ? mfma_logits_row_tiles(s.V) : 0;
+    p.n_cp = n_cp;
+    const bool need_z = bwd || s.dtype == 0;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, REGION_ALIGN); return o; };
+    const size_t N = (size_t)s.N;
+    p.o_wt = take(bwd ? (size_t)s.D * p.Vp * p.es : 0);
+    p.o_logp = take(N * 4);
+    p.o_ell = take(bwd ? N * 4 : 0);
+    p.o_kl = take(bwd ? N * 4 : 0);
+    p.o_clip = take(bwd ? N * 4 : 0);
+    p.o_seq = take(bwd ? 3 * N * 4 : 0);
+    p.fixed_bytes = off;
+    p.o_hc = take((size_t)n_cp * s.D * p.es);
+    p.o_hct = take(bwd ? (size_t)n_cp * s.D * p.es : 0);
+    p.o_part = take((size_t)p.n_tiles * n_cp * 8);
+    p.o_zg = take(need_z ? (size_t)n_cp * p.Vp * p.zs : 0);
+    p.o_gt = take(bwd ? (size_t)n_cp * p.Vp * p.zs : 0);
+    p.o_y = take((size_t)n_cp * 4);
+    p.o_zy = take((size_t)n_cp * 4);
+    p.o_lse = take((size_t)n_cp * 4);
+    p.o_c = take((size_t)n_cp * 4);
+    p.total = off;
+}
+
+int32_t target_chunk(int64_t N) {
+    if (N <= 0) return CHUNK_ALIGN;
+    const int64_t n_chunks = ceil_div(N, CHUNK_MAX);
+    return round_up32(ceil_div(N, n_chunks), CHUNK_ALIGN);
+}
+
+int validate_shape(const dppo_head_shape* s) {
+    if (!s) return fail(DPPO_ERR_INVALID_ARG, "shape is NULL");
+    if (s->dtype != 0 && s->dtype != 1) return fail(DPPO_ERR_UNSUPPORTED, "dtype %d (0 = float32, 1 = bfloat16)", s->dtype);
+    if (s->T < 0 || s->N < 0 || s->N > s->T) return fail(DPPO_ERR_SHAPE, "need 0 <= N <= T (T=%lld N=%lld)", (long long)s->T, (long long)s->N);
+    if (s->D <= 0 || s->V <= 0) return fail(DPPO_ERR_SHAPE, "need D > 0 and V > 0 (D=%d V=%d)", s->D, s->V);
+    if (s->T > 0x7fffffffLL) return fail(DPPO_ERR_UNSUPPORTED, "T above 2^31-1 packed tokens");
+    if (s->dtype == 1 && s->D % 64 != 0) return fail(DPPO_ERR_UNSUPPORTED, "bfloat16 path needs D %% 64 == 0 (D=%d)", s->D);
+    return DPPO_OK;
+}
+
+// Picks the largest chunk that fits `ws_bytes` (at most the balanced target chunk).
+int plan_for(const dppo_head_shape& s, bool bwd, size_t ws_bytes, WsPlan& p) {
+    const int32_t target = target_chunk(s.N);
+    layout(s, bwd, target, p);
+    if (p.total > ws_bytes) {
+        WsPlan q;
+        layout(s, bwd, CHUNK_ALIGN, q);
+        if (q.total > ws_bytes)
+            return fail(DPPO_ERR_WORKSPACE, "workspace of %zu bytes is below the minimum of %zu", ws_bytes, q.total);
+        int32_t lo = 1, hi = target / CHUNK_ALIGN;   // in units of CHUNK_ALIGN: lo fits, hi does not
+        while (hi - lo > 1) {
+            const int32_t mid = (lo + hi) / 2;
+            layout(s, bwd, mid * CHUNK_ALIGN, q);
+            if (q.total <= ws_bytes) lo = mid; else hi = mid;
+        }
+        layout(s, bwd, lo * CHUNK_ALIGN, p);
+    }
+    p.n_chunks = s.N > 0 ? ceil_div(s.N, p.n_cp) : 0;
+    return DPPO_OK;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+struct Regions {
+    char* base;
+    const WsPlan& p;
+    template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(base + off); }
+};
+
+// Forward statistics of one chunk: Hc (and HcT), targets, log-probs, lse. Leaves the chunk's
+// logits in the workspace when keep_z is set (always for float32).
+void chunk_forward(const dppo_head_shape& s, const WsPlan& p, char* ws, const void* H, const void* W,
+                   const int32_t* ids, const int32_t* loss_pos, ChunkView cv, bool bwd, bool keep_z,
+                   float* logp_all, float* lse_all, hipStream_t st) {
+    void* Hc = ws + p.o_hc;
+    void* HcT = bwd ? ws + p.o_hct : nullptr;
+    int32_t* y = reinterpret_cast<int32_t*>(ws + p.o_y);
+    float* zy = reinterpret_cast<float*>(ws + p.o_zy);
+    float* lse_c = reinterpret_cast<float*>(ws + p.o_lse);
+    launch_gather_rows(s.dtype, H, ids, loss_pos, s.T, s.D, s.V, cv, Hc, HcT, y, st);
+    if (s.dtype == 1) {
+        float2* part = reinterpret_cast<float2*>(ws + p.o_part);
+        launch_mfma_logits(W, s.V, s.D, Hc, cv.n_cp, part, keep_z ? ws + p.o_zg : nullptr, p.Vp, p.Vp, st);
+        launch_target_logit(1, Hc, W, y, cv.n_cp, s.D, zy, st);
+        launch_combine_logprob(part, p.n_tiles, zy, cv, lse_c, logp_all, lse_all, st);
+    } else {
+        StoreSpec out{ws + p.o_zg, p.Vp, 0, 0, nullptr, 0};
+        launch_gemm_plain_f32(reinterpret_cast<const float*>(Hc), s.D, reinterpret_cast<const float*>(W), s.D,
+                              cv.n_cp, s.V, s.D, out, st);
+        launch_row_stats_f32(reinterpret_cast<const float*>(ws + p.o_zg), p.Vp, s.V, y, cv, lse_c, logp_all,
+                             lse_all, st);
+    }
+}
+
+}  // namespace
+}  // namespace dppo
+
+using namespace dppo;
+
+extern "C" {
+
+const char* dppo_status_str(int status) {
+    switch (status) {
+        case DPPO_OK: return "ok";
+        case DPPO_ERR_INVALID_ARG: return "invalid argument";
+        case DPPO_ERR_SHAPE: return "invalid shape";
+        case DPPO_ERR_CAPACITY: return "item exceeds packing capacity";
+        case DPPO_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case DPPO_ERR_UNSUPPORTED: return "unsupported shape or dtype";
+        case DPPO_ERR_DEVICE: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+const char* dppo_last_error(void) { return g_err; }
+
+int dppo_select(const dppo_select_params* p, const float* rewards, const float* hist, const float* u_prompt,
+                const float* u_comp, float* adv, float* mean_abs_adv, uint8_t* keep_prompt, uint8_t* keep_comp,
+                float* gamma_q, float* gamma_o, float* coef, int32_t* counts, void* stream) {
+    if (!p) return fail(DPPO_ERR_INVALID_ARG, "params is NULL");
+    if (!rewards || !adv || !mean_abs_adv || !keep_prompt || !keep_comp || !gamma_q || !gamma_o || !coef || !counts)
+        return fail(DPPO_ERR_INVALID_ARG, "a required array pointer is NULL");
+    if (p->Q <= 0 || p->G <= 0) return fail(DPPO_ERR_SHAPE, "need Q > 0 and G > 0 (Q=%d G=%d)", p->Q, p->G);
+    if (p->Q > 16384 || p->G > 1024) return fail(DPPO_ERR_UNSUPPORTED, "Q <= 16384 and G <= 1024 supported (Q=%d G=%d)", p->Q, p->G);
+    if (p->std_ddof != 0 && p->std_ddof != 1) return fail(DPPO_ERR_INVALID_ARG, "std_ddof must be 0 or 1");
+    if (p->G - p->std_ddof < 1) return fail(DPPO_ERR_SHAPE, "G - std_ddof must be at least 1");
+    if (!(p->r_q >= 0.0f && p->r_q < 1.0f) || !(p->r_o >= 0.0f && p->r_o < 1.0f))
+        return fail(DPPO_ERR_INVALID_ARG, "prune probabilities must lie in [0,1) (r_q=%g r_o=%g)", p->r_q, p->r_o);
+    if (!(p->adv_eps >= 0.0f)) return fail(DPPO_ERR_INVALID_ARG, "adv_eps must be >= 0");
+    if (!(p->bottom_frac >= 0.0f && p->bottom_frac <= 1.0f)) return fail(DPPO_ERR_INVALID_ARG, "bottom_frac must lie in [0,1]");
+    const int n_bottom = (int)std::floor((double)p->bottom_frac * (double)p->Q);
+    launch_select(*p, n_bottom, rewards, hist, u_prompt, u_comp, adv, mean_abs_adv, keep_prompt, keep_comp, gamma_q,
+                  gamma_o, coef, counts, (hipStream_t)stream);
+    return check_launch("dppo_select");
+}
+
+int dppo_pack(const dppo_pack_params* p, const int32_t* prompt_len, const int32_t* comp_len, const uint8_t* keep,
+              int32_t* order, int32_t* row_ptr, int32_t* cu_seqlens, int32_t* loss_cu, int32_t* loss_pos,
+              int64_t loss_pos_capacity, int32_t* meta, void* stream) {
+    if (!p) return fail(DPPO_ERR_INVALID_ARG, "params is NULL");
+    if (!prompt_len || !comp_len || !order || !row_ptr || !cu_seqlens || !loss_cu || !loss_pos || !meta)
+        return fail(DPPO_ERR_INVALID_ARG, "a required array pointer is NULL");
+    if (p->n_items <= 0) return fail(DPPO_ERR_SHAPE, "n_items must be positive (%d)", p->n_items);
+    if (p->capacity < 2) return fail(DPPO_ERR_CAPACITY, "capacity must hold at least a 1+1 token sequence (%d)", p->capacity);
+    if (p->n_win < 1) return fail(DPPO_ERR_INVALID_ARG, "n_win must be at least 1 (%d)", p->n_win);
+    if (loss_pos_capacity < 0) return fail(DPPO_ERR_SHAPE, "loss_pos_capacity is negative");
+    launch_pack(*p, prompt_len, comp_len, keep, order, row_ptr, cu_seqlens, loss_cu, loss_pos, loss_pos_capacity,
+                meta, (hipStream_t)stream);
+    return check_launch("dppo_pack");
+}
+
+int dppo_gather_f32(int64_t n, const int32_t* idx, const float* src, float* dst, void* stream) {
+    if (n < 0) return fail(DPPO_ERR_SHAPE, "n is negative");
+    if (n == 0) return DPPO_OK;
+    if (!idx || !src || !dst) return fail(DPPO_ERR_INVALID_ARG, "a required array pointer is NULL");
+    launch_gather_f32(n, idx, src, dst, (hipStream_t)stream);
+    return check_launch("dppo_gather_f32");
+}
+
+size_t dppo_workspace_bytes(const dppo_head_shape* shape, int want_backward) {
+    if (validate_shape(shape) != DPPO_OK) return 0;
+    WsPlan p;
+    layout(*shape, want_backward != 0, target_chunk(shape->N), p);
+    return p.total;
+}
+
+size_t dppo_workspace_min_bytes(const dppo_head_shape* shape, int want_backward) {
+    if (validate_shape(shape) != DPPO_OK) return 0;
+    WsPlan p;
+    layout(*shape, want_backward != 0, CHUNK_ALIGN, p);
+    return p.total;
+}
+
+int dppo_token_logprob(const dppo_head_shape* shape, const void* H, const void* W, const int32_t* ids,
+                       const int32_t* loss_pos, float* logp, float* lse, void* ws, size_t ws_bytes, void* stream) {
+    int rc = validate_shape(shape);
+    if (rc != DPPO_OK) return rc;
+    const dppo_head_shape& s = *shape;
+    if (s.N == 0) return DPPO_OK;
+    if (!H || !W || !ids || !logp) return fail(DPPO_ERR_INVALID_ARG, "a required array pointer is NULL");
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return fail(DPPO_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
+    if (s.dtype == 1 && (!aligned16(H) || !aligned16(W))) return fail(DPPO_ERR_INVALID_ARG, "H and W must be 16-byte aligned");
+    WsPlan p;
+    rc = plan_for(s, false, ws_bytes, p);
+    if (rc != DPPO_OK) return rc;
+    if (s.dtype == 1 && (rc = mfma_setup()) != DPPO_OK) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    char* w = reinterpret_cast<char*>(ws);
+    for (int64_t n0 = 0; n0 < s.N; n0 += p.n_cp) {
+        ChunkView cv;
+        cv.n0 = n0;
+        cv.n_c = (int32_t)((s.N - n0) < p.n_cp ? (s.N - n0) : p.n_cp);
+        cv.n_cp = round_up32(cv.n_c, CHUNK_ALIGN);
+        chunk_forward(s, p, w, H, W, ids, loss_pos, cv, false, false, logp, lse, st);
+    }
+    return check_launch("dppo_token_logprob");
+}
+
+int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, int32_t S, const void* H,
+                      const void* W, const int32_t* ids, const int32_t* loss_pos, const int32_t* loss_cu,
+                      const float* seq_adv, const float* seq_coef, const float* logp_old, const float* logp_ref,
+                      float* loss, float* logp, float* seq_loss, float* stats, void* dH, float* dW, void* ws,
+                      size_t ws_bytes, void* stream) {
+    int rc = validate_shape(shape);
+    if (rc != DPPO_OK) return rc;
+    const dppo_head_shape& s = *shape;
+    if (!lp) return fail(DPPO_ERR_INVALID_ARG, "loss params is NULL");
+    if (!(lp->clip_lo >= 0.0f && lp->clip_lo < 1.0f) || !(lp->clip_hi >= 0.0f))
+        return fail(DPPO_ERR_INVALID_ARG, "need 0 <= clip_lo < 1 and clip_hi >= 0");
+    if (!(lp->beta >= 0.0f)) return fail(DPPO_ERR_INVALID_ARG, "beta must be >= 0");
+    if (S < 0 || (s.N > 0 && S < 1) || (int64_t)S > s.N) return fail(DPPO_ERR_SHAPE, "need 1 <= S <= N when N > 0 (S=%d N=%lld)", S, (long long)s.N);
+    if (!loss || !dH || !dW || !W) return fail(DPPO_ERR_INVALID_ARG, "loss, dH, dW and W must not be NULL");
+    if (s.N > 0 && (!H || !ids || !loss_cu || !seq_adv || !seq_coef || !logp_old || !logp_ref))
+        return fail(DPPO_ERR_INVALID_ARG, "a required array pointer is NULL");
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return fail(DPPO_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
+    if (s.dtype == 1 && (!aligned16(H) || !aligned16(W) || !aligned16(dH) || !aligned16(dW)))
+        return fail(DPPO_ERR_INVALID_ARG, "H, W, dH and dW must be 16-byte aligned");
+    if (lp->recompute_logits != 0 && s.dtype != 1)
+        return fail(DPPO_ERR_UNSUPPORTED, "recompute_logits is a bfloat16-path option");
+    WsPlan p;
+    rc = plan_for(s, true, ws_bytes, p);
+    if (rc != DPPO_OK) return rc;
+    if (s.dtype == 1 && (rc = mfma_setup()) != DPPO_OK) return rc;
+
+    hipStream_t st = (hipStream_t)stream;
+    char* w = reinterpret_cast<char*>(ws);
+    float* logp_all = logp ? logp : reinterpret_cast<float*>(w + p.o_logp);
+    float* ell = reinterpret_cast<float*>(w + p.o_ell);
+    float* kl = reinterpret_cast<float*>(w + p.o_kl);
+    float* clipf = reinterpret_cast<float*>(w + p.o_clip);
+    float* seq_tmp = reinterpret_cast<float*>(w + p.o_seq);
+
+    launch_fill_zero(dH, (size_t)s.T * s.D * p.es, st);
+    if (!lp->accumulate_dW && s.N == 0) launch_fill_zero(dW, (size_t)s.V * s.D * 4, st);
+    if (s.N > 0) launch_transpose_w(s.dtype, W, s.V, s.D, p.Vp, w + p.o_wt, st);
+
+    bool first = true;
+    for (int64_t n0 = 0; n0 < s.N; n0 += p.n_cp) {
+        ChunkView cv;
+        cv.n0 = n0;
+        cv.n_c = (int32_t)((s.N - n0) < p.n_cp ? (s.N - n0) : p.n_cp);
+        cv.n_cp = round_up32(cv.n_c, CHUNK_ALIGN);
+        const bool recompute = lp->recompute_logits != 0;
+        chunk_forward(s, p, w, H, W, ids, loss_pos, cv, true, !recompute, logp_all, nullptr, st);
+
+        TokenLossArgs ta;
+        ta.loss_cu = loss_cu; ta.S = S; ta.seq_adv = seq_adv; ta.seq_coef = seq_coef;
+        ta.logp_old = logp_old; ta.logp_ref = logp_ref; ta.logp = logp_all;
+        ta.lo = (float)(1.0 - (double)lp->clip_lo); ta.hi = (float)(1.0 + (double)lp->clip_hi); ta.beta = lp->beta;
+        ta.c_chunk = reinterpret_cast<float*>(w + p.o_c);
+        ta.ell = ell; ta.kl = kl; ta.clipped = clipf;
+        launch_token_loss(ta, cv, st);
+
+        const int32_t* y = reinterpret_cast<const int32_t*>(w + p.o_y);
+        const float* lse_c = reinterpret_cast<const float*>(w + p.o_lse);
+        void* G = w + p.o_zg;
+        void* GT = w + p.o_gt;
+        if (recompute)
+            launch_mfma_logits_grad(W, s.V, s.D, w + p.o_hc, cv.n_cp, y, lse_c, ta.c_chunk, G, GT, p.Vp, p.Vp, st);
+        else
+            launch_grad_logits(s.dtype, G, GT, s.V, p.Vp, y, lse_c, ta.c_chunk, cv.n_cp, st);
+
+        // dH rows of the chunk: G[n_c, Vp] * WT[D, Vp]^T, scattered to the loss rows of dH
+        StoreSpec oh;
+        oh.out_bf16 = s.dtype == 1; oh.accumulate = 0; oh.ldc = s.D;
+        if (loss_pos) { oh.C = dH; oh.row_map = loss_pos; oh.row_base = n0; }
+        else { oh.C = reinterpret_cast<char*>(dH) + (size_t)n0 * s.D * p.es; oh.row_map = nullptr; oh.row_base = 0; }
+        // dW: GT[V, n_cp] * HcT[D, n_cp]^T
+        StoreSpec ow;
+        ow.C = dW; ow.ldc = s.D; ow.out_bf16 = 0; ow.accumulate = (first && !lp->accumulate_dW) ? 0 : 1;
+        ow.row_map = nullptr; ow.row_base = 0;
+        if (s.dtype == 1) {
+            launch_mfma_gemm(G, p.Vp, w + p.o_wt, p.Vp, cv.n_c, s.D, p.Vp, oh, st);
+            launch_mfma_gemm(GT, cv.n_cp, w + p.o_hct, cv.n_cp, s.V, s.D, cv.n_cp, ow, st);
+        } else {
+            launch_gemm_plain_f32(reinterpret_cast<const float*>(G), p.Vp, reinterpret_cast<const float*>(w + p.o_wt),
+                                  p.Vp, cv.n_c, s.D, p.Vp, oh, st);
+            launch_gemm_plain_f32(reinterpret_cast<const float*>(GT), cv.n_cp,
+                                  reinterpret_cast<const float*>(w + p.o_hct), cv.n_cp, s.V, s.D, cv.n_cp, ow, st);
+        }
+        first = false;
+    }
+
+    SeqReduceArgs ra;
+    ra.loss_cu = loss_cu; ra.S = s.N > 0 ? S : 0; ra.N = s.N; ra.seq_coef = seq_coef;
+    ra.ell = ell; ra.kl = kl; ra.clipped = clipf;
+    ra.seq_mean = seq_tmp; ra.seq_kl = seq_tmp + s.N; ra.seq_clip = seq_tmp + 2 * s.N;
+    ra.seq_loss_out = seq_loss; ra.loss_out = loss; ra.stats_out = stats;
+    launch_seq_reduce(ra, st);
+    return check_launch("dppo_loss_fwd_bwd");
+}
+
+}  // extern "C"

@@ -1,0 +1,116 @@
+// Internal declarations shared by the translation units of the DPPO HIP library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "dppo.h"
+
+namespace dppo {
+
+// Records a formatted message for dppo_last_error() and returns `code`.
+int fail(int code, const char* fmt, ...);
+// Turns the status of the last launch on this thread into a dppo status.
+int check_launch(const char* what);
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// ---- selection (select.hip) -------------------------------------------------
+void launch_select(const dppo_select_params& p, int n_bottom, const float* rewards, const float* hist,
+                   const float* u_prompt, const float* u_comp, float* adv, float* mean_abs_adv,
+                   uint8_t* keep_prompt, uint8_t* keep_comp, float* gamma_q, float* gamma_o,
+                   float* coef, int32_t* counts, hipStream_t st);
+
+// ---- packing (pack.hip) -----------------------------------------------------
+void launch_pack(const dppo_pack_params& p, const int32_t* prompt_len, const int32_t* comp_len,
+                 const uint8_t* keep, int32_t* order, int32_t* row_ptr, int32_t* cu, int32_t* lcu,
+                 int32_t* loss_pos, int64_t loss_pos_capacity, int32_t* meta, hipStream_t st);
+void launch_gather_f32(int64_t n, const int32_t* idx, const float* src, float* dst, hipStream_t st);
+
+// ---- layout / elementwise kernels (head_kernels.hip) -------------------------
+// E = element type of H and W (float or bf16 stored as uint16_t).
+struct ChunkView {
+    int64_t n0;    // first loss token of the chunk
+    int32_t n_c;   // loss tokens in the chunk
+    int32_t n_cp;  // padded chunk rows (multiple of 256)
+};
+
+void launch_fill_zero(void* p, size_t bytes, hipStream_t st);
+// Hc[n_cp, D] = H[row(n0+n)] (zero rows beyond n_c); HcT[D, n_cp] its transpose (may be NULL);
+// y[n] = target id of loss token n0+n (clamped to [0,V)).
+void launch_gather_rows(int dtype, const void* H, const int32_t* ids, const int32_t* loss_pos,
+                        int64_t T, int32_t D, int32_t V, ChunkView cv, void* Hc, void* HcT,
+                        int32_t* y, hipStream_t st);
+// WT[D, Vp] = transpose of W[V, D], columns v >= V zero.
+void launch_transpose_w(int dtype, const void* W, int32_t V, int32_t D, int32_t Vp, void* WT,
+                        hipStream_t st);
+// zy[n] = Hc[n] . W[y[n]] in fp32.
+void launch_target_logit(int dtype, const void* Hc, const void* W, const int32_t* y, int32_t n_cp,
+                         int32_t D, float* zy, hipStream_t st);
+// lse from per-tile partial (max, sumexp) pairs part[tile][n_cp]; logp = zy - lse.
+void launch_combine_logprob(const float2* part, int32_t n_tiles, const float* zy, ChunkView cv,
+                            float* lse_chunk, float* logp_out, float* lse_out, hipStream_t st);
+// fp32 path: row statistics straight from stored logits Z[n_cp, ldz].
+void launch_row_stats_f32(const float* Z, int64_t ldz, int32_t V, const int32_t* y, ChunkView cv,
+                          float* lse_chunk, float* logp_out, float* lse_out, hipStream_t st);
+
+struct TokenLossArgs {
+    const int32_t* loss_cu; int32_t S;
+    const float* seq_adv; const float* seq_coef;
+    const float* logp_old; const float* logp_ref;
+    const float* logp;      // [N] current-policy log-probs (written by the combine step)
+    float lo, hi, beta;     // ratio bounds 1-clip_lo, 1+clip_hi and KL weight
+    float* c_chunk;         // [n_cp] dL/dlogp of the chunk's tokens (0 beyond n_c)
+    float* ell; float* kl; float* clipped;   // [N] per-token loss, KL, clipped-away flag
+};
+void launch_token_loss(const TokenLossArgs& a, ChunkView cv, hipStream_t st);
+
+// In place over the chunk's stored logits: G[n,v] = c[n] (1[v==y[n]] - exp(z - lse[n])) for
+// v < V, 0 for V <= v < Vp; also written transposed to GT[Vp, n_cp].
+// dtype 1: Z is fp16 and G, GT are bf16; dtype 0: all float.
+void launch_grad_logits(int dtype, void* ZG, void* GT, int32_t V, int32_t Vp, const int32_t* y,
+                        const float* lse, const float* c, int32_t n_cp, hipStream_t st);
+
+struct SeqReduceArgs {
+    const int32_t* loss_cu; int32_t S; int64_t N;
+    const float* seq_coef;
+    const float* ell; const float* kl; const float* clipped;
+    float* seq_mean; float* seq_kl; float* seq_clip;   // [S] scratch
+    float* seq_loss_out;                                // [S] or NULL
+    float* loss_out; float* stats_out;                  // [1], [4] or NULL
+};
+void launch_seq_reduce(const SeqReduceArgs& a, hipStream_t st);
+
+// ---- GEMMs -------------------------------------------------------------------
+// Output description of C[M,N] = A[M,K] B[N,K]^T.
+struct StoreSpec {
+    void* C; int64_t ldc;
+    int32_t out_bf16;          // 0: float output, 1: bf16 output
+    int32_t accumulate;        // add to existing contents (float output only)
+    const int32_t* row_map;    // output row = row_map[row_base + m] if not NULL
+    int64_t row_base;
+};
+// fp32 reference-grade GEMM (any sizes), gemm_plain.hip.
+void launch_gemm_plain_f32(const float* A, int64_t lda, const float* B, int64_t ldb, int32_t M,
+                           int32_t N, int32_t K, const StoreSpec& out, hipStream_t st);
+
+// bf16 MFMA GEMMs (gemm_mfma.hip). K must be a multiple of 64; A and B rows may be read up
+// to the next multiple of the tile size, so operands are padded scratch buffers or clamped.
+int mfma_setup();   // one-time kernel attribute setup, returns dppo status
+// Vocabulary GEMM: rows = vocabulary entries (A = W[V,D]), columns = tokens (B = Hc[n_cp,D]).
+// Writes per-(row tile, token) partial (max, sum exp) to part[tile*n_cp + n]; if Z16 != NULL also
+// stores the logits as fp16 to Z16[n*ldz + v] for v < Vp.
+int32_t mfma_logits_row_tiles(int32_t V);
+void launch_mfma_logits(const void* W, int32_t V, int32_t D, const void* Hc, int32_t n_cp,
+                        float2* part, void* Z16, int64_t ldz, int32_t Vp, hipStream_t st);
+// Same GEMM, but the epilogue turns logits straight into gradient entries
+// G[n,v] = c[n] (1[v==y[n]] - exp(z - lse[n])) written as bf16 to G[n*ldg+v] and GT[v*n_cp+n].
+void launch_mfma_logits_grad(const void* W, int32_t V, int32_t D, const void* Hc, int32_t n_cp,
+                             const int32_t* y, const float* lse, const float* c, void* G, void* GT,
+                             int64_t ldg, int32_t Vp, hipStream_t st);
+// Generic C = A B^T with a plain store epilogue.
+void launch_mfma_gemm(const void* A, int64_t lda, const void* B, int64_t ldb, int32_t M, int32_t N,
+                      int32_t K, const StoreSpec& out, hipStream_t st);
+
+}  // namespace dppo

@@ -1,0 +1,366 @@
+// HBM-bound kernels around the vocabulary GEMMs of the LM-head path: row gather and
+// transposes, target logits, combination of per-tile softmax partials, the per-token
+// surrogate + KL terms of Eq. 1 and their derivative, the softmax-gradient pass over a stored
+// logits chunk, and the segmented (per packed sequence) loss reduction.
+// All global accesses are coalesced 16-byte (or full-wave contiguous) transactions; the
+// transposes go through padded LDS tiles.
+#include "dppo_internal.h"
+
+namespace dppo {
+namespace {
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t x) { return __uint_as_float((uint32_t)x << 16); }
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(uint16_t x) { return bf16_to_f32(x); }
+
+// ------------------------------------------------------------------------------------
+__global__ void fill_zero_kernel(uint4* p, size_t n16, unsigned char* tail, size_t ntail) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
+    if (blockIdx.x == 0 && threadIdx.x < ntail) tail[threadIdx.x] = 0;
+}
+
+// ------------------------------------------------------------------------------------
+// Tiled gather + transpose. Source rows come from `src` (row stride ld_src) through an
+// optional row index; rows >= n_valid read as zero. Writes dst[r, c] (optional) and
+// dstT[c, r] (optional) for r < n_rows_out, c < n_cols_out where columns >= n_cols read as 0.
+template <typename E>
+__global__ __launch_bounds__(256) void gather_transpose_kernel(
+    const E* __restrict__ src, int64_t ld_src, const int32_t* __restrict__ row_index, int64_t row_index_base,
+    int64_t src_row0, int64_t src_rows_total, int32_t n_valid, int32_t n_cols, int32_t n_rows_out,
+    int32_t n_cols_out, E* __restrict__ dst, int64_t ld_dst, E* __restrict__ dstT, int64_t ld_dstT) {
+    __shared__ E tile[64][65];
+    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int rr = ty; rr < 64; rr += 4) {
+        const int r = r0 + rr, c = c0 + tx;
+        E v = (E)0;
+        if (r < n_valid && c < n_cols) {
+            int64_t sr = row_index ? (int64_t)row_index[row_index_base + r] : src_row0 + r;
+            sr = sr < 0 ? 0 : (sr >= src_rows_total ? src_rows_total - 1 : sr);
+            v = src[sr * ld_src + c];
+        }
+        tile[rr][tx] = v;
+        if (dst && r < n_rows_out && c < n_cols_out) dst[(int64_t)r * ld_dst + c] = v;
+    }
+    __syncthreads();
+    if (dstT) {
+        for (int cc = ty; cc < 64; cc += 4) {
+            const int c = c0 + cc, r = r0 + tx;
+            if (c < n_cols_out && r < n_rows_out) dstT[(int64_t)c * ld_dstT + r] = tile[tx][cc];
+        }
+    }
+}
+
+__global__ void targets_kernel(const int32_t* __restrict__ ids, const int32_t* __restrict__ loss_pos, int64_t T,
+                               int32_t V, int64_t n0, int32_t n_c, int32_t n_cp, int32_t* __restrict__ y) {
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= n_cp) return;
+    int32_t t = 0;
+    if (n < n_c) {
+        int64_t pos = loss_pos ? (int64_t)loss_pos[n0 + n] + 1 : n0 + n;
+        pos = pos < 0 ? 0 : (pos >= T ? T - 1 : pos);
+        t = ids[pos];
+        t = t < 0 ? 0 : (t >= V ? V - 1 : t);
+    }
+    y[n] = t;
+}
+
+// ------------------------------------------------------------------------------------
+// One wavefront per token: zy[n] = Hc[n] . W[y[n]]
+template <typename E>
+__global__ __launch_bounds__(256) void target_logit_kernel(const E* __restrict__ Hc, const E* __restrict__ W,
+                                                           const int32_t* __restrict__ y, int32_t n_cp, int32_t D,
+                                                           float* __restrict__ zy) {
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (n >= n_cp) return;
+    const E* h = Hc + (size_t)n * D;
+    const E* w = W + (size_t)y[n] * D;
+    float s = 0.0f;
+    for (int d = lane; d < D; d += 64) s = fmaf(to_f32(h[d]), to_f32(w[d]), s);
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if (lane == 0) zy[n] = s;
+}
+
+// ------------------------------------------------------------------------------------
+__global__ void combine_logprob_kernel(const float2* __restrict__ part, int32_t n_tiles, const float* __restrict__ zy,
+                                       int64_t n0, int32_t n_c, int32_t n_cp, float* __restrict__ lse_chunk,
+                                       float* __restrict__ logp_out, float* __restrict__ lse_out) {
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= n_cp) return;
+    if (n >= n_c) { lse_chunk[n] = 0.0f; return; }
+    float m = -__builtin_inff();
+    for (int t = 0; t < n_tiles; ++t) m = fmaxf(m, part[(size_t)t * n_cp + n].x);
+    float s = 0.0f;
+    for (int t = 0; t < n_tiles; ++t) {
+        const float2 p = part[(size_t)t * n_cp + n];
+        s += p.y * expf(p.x - m);
+    }
+    const float lse = m + logf(s);
+    lse_chunk[n] = lse;
+    logp_out[n0 + n] = zy[n] - lse;
+    if (lse_out) lse_out[n0 + n] = lse;
+}
+
+// fp32 path: one workgroup per token over the stored logits row.
+__global__ __launch_bounds__(256) void row_stats_kernel(const float* __restrict__ Z, int64_t ldz, int32_t V,
+                                                        const int32_t* __restrict__ y, int64_t n0, int32_t n_c,
+                                                        float* __restrict__ lse_chunk, float* __restrict__ logp_out,
+                                                        float* __restrict__ lse_out) {
+    __shared__ float red[256];
+    const int n = blockIdx.x;
+    if (n >= n_c) { if (threadIdx.x == 0) lse_chunk[n] = 0.0f; return; }
+    const float* z = Z + (size_t)n * ldz;
+    float m = -__builtin_inff();
+    for (int v = threadIdx.x; v < V; v += 256) m = fmaxf(m, z[v]);
+    red[threadIdx.x] = m;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if (threadIdx.x < s) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + s]);
+        __syncthreads();
+    }
+    m = red[0];
+    __syncthreads();
+    float sum = 0.0f;
+    for (int v = threadIdx.x; v < V; v += 256) sum += expf(z[v] - m);
+    red[threadIdx.x] = sum;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if (threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const float lse = m + logf(red[0]);
+        lse_chunk[n] = lse;
+        logp_out[n0 + n] = z[y[n]] - lse;
+        if (lse_out) lse_out[n0 + n] = lse;
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// Per-token terms of Eq. 1 and d(loss)/d(logp), weighted by seq_coef / C_s.
+__global__ void token_loss_kernel(TokenLossArgs a, int64_t n0, int32_t n_c, int32_t n_cp) {
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= n_cp) return;
+    if (n >= n_c) { a.c_chunk[n] = 0.0f; return; }
+    const int64_t gi = n0 + n;
+    int lo = 0, hi = a.S;          // largest s with loss_cu[s] <= gi
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if ((int64_t)a.loss_cu[mid] <= gi) lo = mid; else hi = mid;
+    }
+    const int s = lo;
+    const float A = a.seq_adv[s];
+    const float w = a.seq_coef[s] / (float)(a.loss_cu[s + 1] - a.loss_cu[s]);
+    const float lp = a.logp[gi];
+    const float d_old = lp - a.logp_old[gi];
+    const float d_ref = a.logp_ref[gi] - lp;
+    const float rho = expf(d_old);
+    const float unclipped = rho * A;
+    const float clipped = fminf(fmaxf(rho, a.lo), a.hi) * A;
+    const float sur = fminf(unclipped, clipped);
+    const float em1 = expm1f(d_ref);             // rho_hat - 1
+    const float kl = em1 - d_ref;                // rho_hat - log rho_hat - 1
+    const bool away = (A > 0.0f && rho > a.hi) || (A < 0.0f && rho < a.lo);
+    const float g = (away ? 0.0f : -A * rho) - a.beta * em1;
+    a.ell[gi] = -sur + a.beta * kl;
+    a.kl[gi] = kl;
+    a.clipped[gi] = away ? 1.0f : 0.0f;
+    a.c_chunk[n] = w * g;
+}
+
+// ------------------------------------------------------------------------------------
+// Softmax-gradient pass over a stored logits chunk, 64 tokens x 64 vocabulary entries per
+// workgroup: in place Z[n,v] -> G[n,v], and the transposed copy GT[v,n] through LDS.
+template <typename ZT, typename GT_, typename ZV, typename GV>
+__global__ __launch_bounds__(256) void grad_logits_kernel(void* ZG, GT_* __restrict__ GTp, int32_t V, int64_t ld,
+                                                          const int32_t* __restrict__ y, const float* __restrict__ lse,
+                                                          const float* __restrict__ cvec, int64_t n_cp) {
+    __shared__ GT_ tile[64][64 + 8];   // [v][n]
+    const int v0 = blockIdx.x * 64, nb = blockIdx.y * 64;
+    const int t = threadIdx.x;
+    const int kc = t & 7;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int r = (t >> 3) + pass * 32;
+        const int64_t n = nb + r;
+        const float l = lse[n], cn = cvec[n];
+        const int yt = y[n];
+        char* p = reinterpret_cast<char*>(ZG) + ((size_t)n * ld + v0 + kc * 8) * sizeof(ZT);
+        const ZV z = *reinterpret_cast<const ZV*>(p);
+        GV g;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int v = v0 + kc * 8 + q;
+            const float pr = expf((float)z[q] - l);
+            float gv = cn * ((v == yt ? 1.0f : 0.0f) - pr);
+            gv = v < V ? gv : 0.0f;
+            g[q] = (GT_)gv;
+            tile[kc * 8 + q][r] = g[q];
+        }
+        *reinterpret_cast<GV*>(p) = g;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int v = (t >> 3) + pass * 32;
+        GV g;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) g[q] = tile[v][kc * 8 + q];
+        *reinterpret_cast<GV*>(GTp + (size_t)(v0 + v) * n_cp + nb + kc * 8) = g;
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// One workgroup per packed sequence: token-mean loss, KL sum, clipped count.
+__global__ __launch_bounds__(256) void seq_reduce_kernel(SeqReduceArgs a) {
+    __shared__ float r0[256], r1[256], r2[256];
+    for (int s = blockIdx.x; s < a.S; s += gridDim.x) {
+        const int b = a.loss_cu[s], e = a.loss_cu[s + 1];
+        float x0 = 0.0f, x1 = 0.0f, x2 = 0.0f;
+        for (int i = b + threadIdx.x; i < e; i += 256) { x0 += a.ell[i]; x1 += a.kl[i]; x2 += a.clipped[i]; }
+        r0[threadIdx.x] = x0; r1[threadIdx.x] = x1; r2[threadIdx.x] = x2;
+        __syncthreads();
+        for (int st = 128; st > 0; st >>= 1) {
+            if (threadIdx.x < st) {
+                r0[threadIdx.x] += r0[threadIdx.x + st];
+                r1[threadIdx.x] += r1[threadIdx.x + st];
+                r2[threadIdx.x] += r2[threadIdx.x + st];
+            }
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) {
+            const float mean = r0[0] / (float)(e - b);
+            a.seq_mean[s] = mean;
+            a.seq_kl[s] = r1[0];
+            a.seq_clip[s] = r2[0];
+            if (a.seq_loss_out) a.seq_loss_out[s] = mean;
+        }
+        __syncthreads();
+    }
+}
+
+// One workgroup: weighted sum over sequences in fp64, fixed order.
+__global__ __launch_bounds__(256) void final_reduce_kernel(SeqReduceArgs a) {
+    __shared__ double r0[256], r1[256], r2[256];
+    double x0 = 0.0, x1 = 0.0, x2 = 0.0;
+    for (int s = threadIdx.x; s < a.S; s += 256) {
+        x0 += (double)a.seq_coef[s] * (double)a.seq_mean[s];
+        x1 += (double)a.seq_kl[s];
+        x2 += (double)a.seq_clip[s];
+    }
+    r0[threadIdx.x] = x0; r1[threadIdx.x] = x1; r2[threadIdx.x] = x2;
+    __syncthreads();
+    for (int st = 128; st > 0; st >>= 1) {
+        if (threadIdx.x < st) {
+            r0[threadIdx.x] += r0[threadIdx.x + st];
+            r1[threadIdx.x] += r1[threadIdx.x + st];
+            r2[threadIdx.x] += r2[threadIdx.x + st];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        a.loss_out[0] = (float)r0[0];
+        if (a.stats_out) {
+            const double n = a.N > 0 ? (double)a.N : 1.0;
+            a.stats_out[0] = (float)(r1[0] / n);
+            a.stats_out[1] = (float)(r2[0] / n);
+            a.stats_out[2] = (float)a.N;
+            a.stats_out[3] = 0.0f;
+        }
+    }
+}
+
+}  // namespace
+
+// ======================================================================================
+void launch_fill_zero(void* p, size_t bytes, hipStream_t st) {
+    if (bytes == 0) return;
+    const size_t n16 = bytes / 16, ntail = bytes % 16;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    if (blocks == 0) blocks = 1;
+    fill_zero_kernel<<<(unsigned)blocks, 256, 0, st>>>(reinterpret_cast<uint4*>(p), n16,
+                                                       reinterpret_cast<unsigned char*>(p) + n16 * 16, ntail);
+}
+
+void launch_gather_rows(int dtype, const void* H, const int32_t* ids, const int32_t* loss_pos, int64_t T,
+                        int32_t D, int32_t V, ChunkView cv, void* Hc, void* HcT, int32_t* y, hipStream_t st) {
+    dim3 grid((unsigned)ceil_div(D, 64), (unsigned)(cv.n_cp / 64));
+    if (dtype == 1) {
+        gather_transpose_kernel<uint16_t><<<grid, 256, 0, st>>>(
+            reinterpret_cast<const uint16_t*>(H), D, loss_pos, cv.n0, cv.n0, T, cv.n_c, D, cv.n_cp, D,
+            reinterpret_cast<uint16_t*>(Hc), D, reinterpret_cast<uint16_t*>(HcT), cv.n_cp);
+    } else {
+        gather_transpose_kernel<float><<<grid, 256, 0, st>>>(
+            reinterpret_cast<const float*>(H), D, loss_pos, cv.n0, cv.n0, T, cv.n_c, D, cv.n_cp, D,
+            reinterpret_cast<float*>(Hc), D, reinterpret_cast<float*>(HcT), cv.n_cp);
+    }
+    targets_kernel<<<(unsigned)ceil_div(cv.n_cp, 256), 256, 0, st>>>(ids, loss_pos, T, V, cv.n0, cv.n_c, cv.n_cp, y);
+}
+
+void launch_transpose_w(int dtype, const void* W, int32_t V, int32_t D, int32_t Vp, void* WT, hipStream_t st) {
+    dim3 grid((unsigned)ceil_div(D, 64), (unsigned)ceil_div(Vp, 64));
+    if (dtype == 1) {
+        gather_transpose_kernel<uint16_t><<<grid, 256, 0, st>>>(reinterpret_cast<const uint16_t*>(W), D, nullptr, 0,
+                                                                0, V, V, D, Vp, D, nullptr, 0,
+                                                                reinterpret_cast<uint16_t*>(WT), Vp);
+    } else {
+        gather_transpose_kernel<float><<<grid, 256, 0, st>>>(reinterpret_cast<const float*>(W), D, nullptr, 0, 0, V,
+                                                             V, D, Vp, D, nullptr, 0, reinterpret_cast<float*>(WT),
+                                                             Vp);
+    }
+}
+
+void launch_target_logit(int dtype, const void* Hc, const void* W, const int32_t* y, int32_t n_cp, int32_t D,
+                         float* zy, hipStream_t st) {
+    const unsigned blocks = (unsigned)ceil_div(n_cp, 4);
+    if (dtype == 1)
+        target_logit_kernel<uint16_t><<<blocks, 256, 0, st>>>(reinterpret_cast<const uint16_t*>(Hc),
+                                                              reinterpret_cast<const uint16_t*>(W), y, n_cp, D, zy);
+    else
+        target_logit_kernel<float><<<blocks, 256, 0, st>>>(reinterpret_cast<const float*>(Hc),
+                                                           reinterpret_cast<const float*>(W), y, n_cp, D, zy);
+}
+
+void launch_combine_logprob(const float2* part, int32_t n_tiles, const float* zy, ChunkView cv, float* lse_chunk,
+                            float* logp_out, float* lse_out, hipStream_t st) {
+    combine_logprob_kernel<<<(unsigned)ceil_div(cv.n_cp, 64), 64, 0, st>>>(part, n_tiles, zy, cv.n0, cv.n_c, cv.n_cp,
+                                                                            lse_chunk, logp_out, lse_out);
+}
+
+void launch_row_stats_f32(const float* Z, int64_t ldz, int32_t V, const int32_t* y, ChunkView cv, float* lse_chunk,
+                          float* logp_out, float* lse_out, hipStream_t st) {
+    row_stats_kernel<<<(unsigned)cv.n_cp, 256, 0, st>>>(Z, ldz, V, y, cv.n0, cv.n_c, lse_chunk, logp_out, lse_out);
+}
+
+void launch_token_loss(const TokenLossArgs& a, ChunkView cv, hipStream_t st) {
+    token_loss_kernel<<<(unsigned)ceil_div(cv.n_cp, 256), 256, 0, st>>>(a, cv.n0, cv.n_c, cv.n_cp);
+}
+
+void launch_grad_logits(int dtype, void* ZG, void* GT, int32_t V, int32_t Vp, const int32_t* y, const float* lse,
+                        const float* c, int32_t n_cp, hipStream_t st) {
+    dim3 grid((unsigned)(Vp / 64), (unsigned)(n_cp / 64));
+    if (dtype == 1)
+        grad_logits_kernel<_Float16, __bf16, f16x8, bf16x8><<<grid, 256, 0, st>>>(
+            ZG, reinterpret_cast<__bf16*>(GT), V, Vp, y, lse, c, n_cp);
+    else
+        grad_logits_kernel<float, float, f32x8, f32x8><<<grid, 256, 0, st>>>(ZG, reinterpret_cast<float*>(GT), V, Vp,
+                                                                             y, lse, c, n_cp);
+}
+
+void launch_seq_reduce(const SeqReduceArgs& a, hipStream_t st) {
+    if (a.S > 0) {
+        const unsigned blocks = a.S < 4096 ? (unsigned)a.S : 4096u;
+        seq_reduce_kernel<<<blocks, 256, 0, st>>>(a);
+    }
+    final_reduce_kernel<<<1, 256, 0, st>>>(a);
+}
+
+}  // namespace dppo

@@ -1,0 +1,143 @@
+"""GPU parity of dppo_select and dppo_pack against the CPU oracle: masks, counts and every
+packing offset bit-exact; float outputs to float32 rounding."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as WL
+from oracle import dppo_oracle as O
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2603_04135_amd as P
+    P.load()
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return P
+
+
+def _cmp_select(P, rewards, hist, up, uc, r_q, r_o, ddof=1, eps=1e-6, bottom=0.5):
+    ref = O.select(rewards, hist, up, uc, r_q, r_o, ddof=ddof, eps=eps, bottom_frac=bottom)
+    got = P.dppo_select(rewards, hist, up, uc, r_q, r_o, adv_eps=eps, std_ddof=ddof, bottom_frac=bottom, device=DEV)
+    g = {k: v.cpu().numpy() for k, v in got.items()}
+    assert np.array_equal(g["keep_prompt"], ref["keep_prompt"])
+    assert np.array_equal(g["keep_comp"], ref["keep_comp"])
+    assert np.array_equal(g["counts"], ref["counts"])
+    for k in ("adv", "mean_abs_adv", "gamma_q", "gamma_o", "coef"):
+        assert np.allclose(g[k], ref[k], rtol=2e-6, atol=1e-9), k
+    return ref, g
+
+
+@pytest.mark.parametrize("name", list(WL.WORKLOADS))
+def test_select_matches_oracle_on_workloads(lib, name):
+    rb = WL.make_rollout(name)
+    wl = rb.wl
+    ref, _ = _cmp_select(lib, rb.rewards, rb.hist, rb.u_prompt, rb.u_comp, wl.r_q, wl.r_o)
+    assert 0 < ref["keep_comp"].sum() < wl.Q * wl.G
+    # first epoch: no history, prompt pruning skipped
+    _cmp_select(lib, rb.rewards, None, None, rb.u_comp, wl.r_q, wl.r_o)
+    # no pruning at all recovers plain GRPO weights
+    ref, g = _cmp_select(lib, rb.rewards, None, None, None, wl.r_q, wl.r_o)
+    assert np.allclose(g["coef"], 1.0 / (wl.Q * wl.G), rtol=1e-6)
+
+
+def test_select_edge_cases(lib):
+    rng = np.random.default_rng(5)
+    # balanced and constant binary groups (ties decide the whole candidate set), odd Q, tied history
+    for G in (2, 4, 8, 16):
+        r = np.zeros((7, G), dtype=np.float32)
+        r[0, : G // 2] = 1; r[1, :] = 1; r[3, :1] = 1; r[4, : G - 1] = 1; r[5, ::2] = 1; r[6, : G // 2 + 1] = 1
+        hist = np.array([0.2, 0.0, 0.2, 0.0, 0.7, 0.0, 0.2], dtype=np.float32)
+        for seed in range(3):
+            rr = np.random.default_rng(seed)
+            _cmp_select(lib, r, hist, rr.random(7, dtype=np.float32), rr.random((7, G), dtype=np.float32), 0.5, 0.5)
+    # G = 1 needs the population std; real-valued rewards; ddof 0; other bottom fractions
+    _cmp_select(lib, rng.random((5, 1)).astype(np.float32), None, None, rng.random((5, 1), dtype=np.float32), 0.3, 0.9, ddof=0)
+    r = rng.normal(size=(33, 6)).astype(np.float32)
+    _cmp_select(lib, r, rng.random(33).astype(np.float32), rng.random(33, dtype=np.float32),
+                rng.random((33, 6), dtype=np.float32), 0.7, 0.25, ddof=0, bottom=0.3)
+    # uniforms that prune everything that can be pruned (whole groups disappear)
+    r = (rng.random((6, 4)) < 0.5).astype(np.float32)
+    ref, _ = _cmp_select(lib, r, np.zeros(6, np.float32), np.zeros(6, np.float32), np.zeros((6, 4), np.float32), 0.9, 0.9)
+    assert ref["keep_prompt"].sum() == 3
+
+
+def test_select_rejects_bad_arguments(lib):
+    r = np.zeros((2, 2), dtype=np.float32)
+    with pytest.raises(lib.DppoError):
+        lib.dppo_select(r, None, None, None, 1.0, 0.5, device=DEV)
+    with pytest.raises(lib.DppoError):
+        lib.dppo_select(np.zeros((2, 1), np.float32), None, None, None, 0.5, 0.5, std_ddof=1, device=DEV)
+
+
+def _cmp_pack(P, pl, cl, keep, cap, n_win):
+    ref = O.pack(pl, cl, keep, cap, n_win)
+    got = P.dppo_pack(pl, cl, keep, cap, n_win, device=DEV)
+    assert got["device_status"] == 0
+    assert (got["n_rows"], got["T"], got["N"], got["S"]) == (ref["n_rows"], ref["T"], ref["N"], ref["S"])
+    for k in ("order", "row_ptr", "cu_seqlens", "loss_cu", "loss_pos"):
+        assert np.array_equal(got[k].cpu().numpy(), ref[k]), k
+    return ref
+
+
+@pytest.mark.parametrize("name", list(WL.WORKLOADS))
+def test_pack_matches_oracle_on_workloads(lib, name):
+    rb = WL.make_rollout(name)
+    wl = rb.wl
+    keep = O.select(rb.rewards, rb.hist, rb.u_prompt, rb.u_comp, wl.r_q, wl.r_o)["keep_comp"].reshape(-1)
+    n = int(keep.sum())
+    for n_win in sorted({1, 2, wl.n_win, 64, 65, n, n + 3}):
+        ref = _cmp_pack(lib, rb.item_prompt_len, rb.item_comp_len, keep, wl.capacity, n_win)
+    assert ref["T"] > 0
+    _cmp_pack(lib, rb.item_prompt_len, rb.item_comp_len, None, wl.capacity, wl.n_win)
+
+
+def test_pack_edge_cases(lib):
+    rng = np.random.default_rng(17)
+    for trial in range(40):
+        n = int(rng.integers(1, 300))
+        cap = int(rng.integers(4, 200))
+        pl = rng.integers(1, cap // 2 + 1, size=n).astype(np.int32)
+        cl = rng.integers(1, cap - pl + 1).astype(np.int32)
+        if trial % 4 == 0:
+            pl[0], cl[0] = 1, cap - 1                       # an item that fills a row exactly
+        keep = (rng.random(n) < 0.7).astype(np.uint8) if trial % 2 else None
+        if keep is not None and keep.sum() == 0:
+            keep[0] = 1
+        for n_win in (1, 2, 7, 64, 130, n + 1):
+            _cmp_pack(lib, pl, cl, keep, cap, n_win)
+    # one-token prompts and completions
+    _cmp_pack(lib, np.ones(100, np.int32), np.ones(100, np.int32), None, 7, 5)
+    # everything pruned: empty result, no error
+    got = lib.dppo_pack(np.array([3, 4], np.int32), np.array([2, 2], np.int32), np.zeros(2, np.uint8), 16, 4, device=DEV)
+    assert (got["n_rows"], got["T"], got["N"], got["S"], got["device_status"]) == (0, 0, 0, 0, 0)
+
+
+def test_pack_reports_device_detected_errors(lib):
+    # item longer than the window
+    got = lib.dppo_pack(np.array([3, 9], np.int32), np.array([2, 8], np.int32), None, 16, 4, device=DEV)
+    assert got["device_status"] == 1 and got["S"] == 0 and got["T"] == 0
+    # empty completion
+    got = lib.dppo_pack(np.array([3, 3], np.int32), np.array([2, 0], np.int32), None, 16, 4, device=DEV)
+    assert got["device_status"] == 1
+    # ... but not if that item is pruned
+    got = lib.dppo_pack(np.array([3, 9], np.int32), np.array([2, 8], np.int32), np.array([1, 0], np.uint8), 16, 4, device=DEV)
+    assert got["device_status"] == 0 and got["S"] == 1
+    # loss_pos buffer too small
+    got = lib.dppo_pack(np.array([3, 3], np.int32), np.array([5, 5], np.int32), None, 16, 4, loss_pos_capacity=9, device=DEV)
+    assert got["device_status"] == 2
+    with pytest.raises(lib.DppoError):
+        lib.dppo_pack(np.array([3], np.int32), np.array([2], np.int32), None, 16, 0, device=DEV)
+
+
+def test_gather_puts_weights_in_packed_order(lib):
+    rb = WL.make_rollout("small")
+    wl = rb.wl
+    sel = O.select(rb.rewards, rb.hist, rb.u_prompt, rb.u_comp, wl.r_q, wl.r_o)
+    pk = O.pack(rb.item_prompt_len, rb.item_comp_len, sel["keep_comp"].reshape(-1), wl.capacity, wl.n_win)
+    coef = torch.as_tensor(sel["coef"].astype(np.float32), device=DEV)
+    got = lib.dppo_gather_f32(torch.as_tensor(pk["order"], device=DEV), coef).cpu().numpy()
+    assert np.array_equal(got, sel["coef"].astype(np.float32).reshape(-1)[pk["order"]])

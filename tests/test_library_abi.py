@@ -1,0 +1,73 @@
+"""Host-only checks of the HIP library: it loads, exports every symbol the header declares,
+and rejects bad arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2603_04135_amd as P
+    if not os.path.exists(P.library_path()):
+        import __graft_entry__
+        __graft_entry__.build()
+    return P.load()
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "dppo.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dppo_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    from paper_2603_04135_amd.binding import EXPORTS
+    declared = _declared_symbols()
+    assert declared, "no declarations found in include/dppo.h"
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert sorted(EXPORTS) == declared
+
+
+def test_status_strings(lib):
+    assert lib.dppo_status_str(0) == b"ok"
+    assert lib.dppo_status_str(3) and lib.dppo_status_str(99) == b"unknown status"
+    assert lib.dppo_last_error() is not None
+
+
+def test_host_side_validation_launches_nothing(lib):
+    from paper_2603_04135_amd.binding import HeadShape, LossParams, PackParams, SelectParams
+    one = ctypes.c_void_p(256)   # never dereferenced: validation fails first
+    sp = SelectParams(4, 4, 1.0, 0.5, 1e-6, 1, 0.5)       # r_q outside [0,1)
+    assert lib.dppo_select(ctypes.byref(sp), *([one] * 12), None) == 1
+    assert b"[0,1)" in lib.dppo_last_error()
+    sp = SelectParams(4, 1, 0.5, 0.5, 1e-6, 1, 0.5)       # sample std of one completion
+    assert lib.dppo_select(ctypes.byref(sp), *([one] * 12), None) == 2
+    sp = SelectParams(4, 4, 0.5, 0.5, 1e-6, 1, 0.5)
+    assert lib.dppo_select(ctypes.byref(sp), None, *([one] * 11), None) == 1
+    pp = PackParams(0, 16, 4)
+    assert lib.dppo_pack(ctypes.byref(pp), *([one] * 8), 10, one, None) == 2
+    pp = PackParams(4, 16, 0)
+    assert lib.dppo_pack(ctypes.byref(pp), *([one] * 8), 10, one, None) == 1
+    hs = HeadShape(100, 50, 72, 1000, 1)                  # bf16 needs D % 64 == 0
+    assert lib.dppo_token_logprob(ctypes.byref(hs), *([one] * 7), 1 << 20, None) == 5
+    assert lib.dppo_workspace_bytes(ctypes.byref(hs), 1) == 0
+    hs = HeadShape(100, 200, 64, 1000, 1)                 # N > T
+    assert lib.dppo_token_logprob(ctypes.byref(hs), *([one] * 7), 1 << 20, None) == 2
+    hs = HeadShape(100, 50, 64, 1000, 1)
+    lp = LossParams(0.2, 0.2, 0.04, 0, 0)
+    assert lib.dppo_loss_fwd_bwd(ctypes.byref(hs), ctypes.byref(lp), 3, *([one] * 15), one, 1024, None) == 4
+    assert lib.dppo_token_logprob(ctypes.byref(hs), *([one] * 6), None, 1 << 20, None) == 4
+
+
+def test_workspace_sizes(lib):
+    from paper_2603_04135_amd.binding import HeadShape
+    hs = HeadShape(370000, 310000, 2560, 151936, 1)
+    rec = lib.dppo_workspace_bytes(ctypes.byref(hs), 1)
+    mn = lib.dppo_workspace_min_bytes(ctypes.byref(hs), 1)
+    fwd = lib.dppo_workspace_bytes(ctypes.byref(hs), 0)
+    assert 0 < fwd < mn < rec < 40 * 2**30
