@@ -309,8 +309,9 @@ struct EpiLogitsGrad {
                             const float p = __builtin_amdgcn_exp2f((acc[mi][ni][4 * g + q] - l) * LOG2E);
                             float gv = cn * ((v == yt ? 1.0f : 0.0f) - p);
                             gv = v < V ? gv : 0.0f;
-                            h[q] = (__bf16)gv;
-                            GT[(int64_t)v * n_cp + col] = __builtin_bit_cast(uint16_t, h[q]);
+                            const __bf16 b = (__bf16)gv;   // scalar copy: reading h[q] back right after writing it miscompiles
+                            h[q] = b;
+                            GT[(int64_t)v * n_cp + col] = __builtin_bit_cast(uint16_t, b);
                         }
                         *reinterpret_cast<bf16x4*>(G + col * ldg + v0) = h;
                     }

@@ -201,8 +201,9 @@ __global__ __launch_bounds__(256) void grad_logits_kernel(void* ZG, GT_* __restr
             const float pr = expf((float)z[q] - l);
             float gv = cn * ((v == yt ? 1.0f : 0.0f) - pr);
             gv = v < V ? gv : 0.0f;
-            g[q] = (GT_)gv;
-            tile[kc * 8 + q][r] = g[q];
+            const GT_ b = (GT_)gv;   // keep the scalar: reading g[q] back right after writing it miscompiles
+            g[q] = b;
+            tile[kc * 8 + q][r] = b;
         }
         *reinterpret_cast<GV*>(p) = g;
     }
