@@ -180,6 +180,23 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* p, i
                       void* dH, float* dW,
                       void* ws, size_t ws_bytes, void* stream);
 
+/* --------------------------------------------------------------------------------
+ * Optional stage timing, for benchmarks. While enabled, dppo_token_logprob and
+ * dppo_loss_fwd_bwd record a pair of HIP events around each launch of the stages below, on
+ * the caller's stream (the kernels themselves are unchanged). dppo_timing_read waits for the
+ * recorded events (a host-side wait), returns the summed milliseconds and the launch count
+ * of every stage since the last reset, and with reset != 0 forgets them. Host arrays.
+ */
+enum {
+    DPPO_STAGE_LOGITS_GEMM = 0, /* vocabulary GEMM with the online max / sum-exp epilogue */
+    DPPO_STAGE_GRAD_LOGITS = 1, /* softmax-gradient pass over the stored logits chunk     */
+    DPPO_STAGE_DH_GEMM = 2,     /* dH = G W                                               */
+    DPPO_STAGE_DW_GEMM = 3,     /* dW += G^T H                                            */
+    DPPO_N_STAGES = 4
+};
+int dppo_timing_enable(int on);
+int dppo_timing_read(double* ms /* [DPPO_N_STAGES] */, int64_t* launches /* [DPPO_N_STAGES] */, int reset);
+
 #ifdef __cplusplus
 }
 #endif

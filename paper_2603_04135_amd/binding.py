@@ -18,7 +18,9 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdppo_hi
 _lib = None
 
 EXPORTS = ["dppo_status_str", "dppo_last_error", "dppo_select", "dppo_pack", "dppo_gather_f32",
-           "dppo_workspace_bytes", "dppo_workspace_min_bytes", "dppo_token_logprob", "dppo_loss_fwd_bwd"]
+           "dppo_workspace_bytes", "dppo_workspace_min_bytes", "dppo_token_logprob", "dppo_loss_fwd_bwd",
+           "dppo_timing_enable", "dppo_timing_read"]
+STAGES = ["logits_gemm", "grad_logits", "dh_gemm", "dw_gemm"]
 
 
 class DppoError(RuntimeError):
@@ -77,6 +79,10 @@ def load():
     lib.dppo_loss_fwd_bwd.restype = c_int
     lib.dppo_loss_fwd_bwd.argtypes = ([POINTER(HeadShape), POINTER(LossParams), c_int32] + [c_void_p] * 16
                                       + [c_size_t, c_void_p])
+    lib.dppo_timing_enable.restype = c_int
+    lib.dppo_timing_enable.argtypes = [c_int]
+    lib.dppo_timing_read.restype = c_int
+    lib.dppo_timing_read.argtypes = [POINTER(ctypes.c_double), POINTER(c_int64), c_int]
     _lib = lib
     return lib
 
@@ -255,3 +261,16 @@ def dppo_loss_fwd_bwd(H, W, ids, loss_pos, loss_cu, seq_adv, seq_coef, logp_old,
     res["dH"] = dH
     res["dW"] = dW
     return res
+
+
+def dppo_timing_enable(on: bool) -> None:
+    _check(load().dppo_timing_enable(1 if on else 0), "dppo_timing_enable")
+
+
+def dppo_timing_read(reset: bool = True) -> dict:
+    """{stage: (milliseconds, launches)} summed since the last reset."""
+    n = len(STAGES)
+    ms = (ctypes.c_double * n)()
+    cnt = (c_int64 * n)()
+    _check(load().dppo_timing_read(ms, cnt, 1 if reset else 0), "dppo_timing_read")
+    return {name: (float(ms[i]), int(cnt[i])) for i, name in enumerate(STAGES)}

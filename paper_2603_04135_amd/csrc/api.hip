@@ -4,6 +4,8 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
+#include <vector>
 
 #include "dppo_internal.h"
 
@@ -26,6 +28,39 @@ int check_launch(const char* what) {
 }
 
 namespace {
+
+// ---- optional stage timing (benchmarks): HIP events around the launches of each stage, on the
+// caller's stream; read back with dppo_timing_read ---------------------------------------------
+struct TimingState {
+    std::mutex mu;
+    bool on = false;
+    struct Span { int stage; hipEvent_t a, b; };
+    std::vector<Span> spans;
+    std::vector<hipEvent_t> pool;
+    hipEvent_t get() {
+        if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) return nullptr;
+        return e;
+    }
+};
+TimingState g_timing;
+
+struct StageTimer {
+    int stage; hipStream_t st; hipEvent_t a = nullptr, b = nullptr;
+    StageTimer(int stage_, hipStream_t st_) : stage(stage_), st(st_) {
+        std::lock_guard<std::mutex> lk(g_timing.mu);
+        if (!g_timing.on || g_timing.spans.size() >= (1u << 16)) return;
+        a = g_timing.get(); b = g_timing.get();
+        if (a && b) (void)hipEventRecord(a, st); else a = b = nullptr;
+    }
+    ~StageTimer() {
+        if (!a) return;
+        (void)hipEventRecord(b, st);
+        std::lock_guard<std::mutex> lk(g_timing.mu);
+        g_timing.spans.push_back({stage, a, b});
+    }
+};
 
 constexpr int32_t CHUNK_ALIGN = 256;      // token-chunk granularity (= GEMM tile edge)
 constexpr int32_t CHUNK_MAX = 32768;      // largest token chunk
@@ -131,7 +166,10 @@ void chunk_forward(const dppo_head_shape& s, const WsPlan& p, char* ws, const vo
     launch_gather_rows(s.dtype, H, ids, loss_pos, s.T, s.D, s.V, cv, Hc, HcT, y, st);
     if (s.dtype == 1) {
         float2* part = reinterpret_cast<float2*>(ws + p.o_part);
-        launch_mfma_logits(W, s.V, s.D, Hc, cv.n_cp, part, keep_z ? ws + p.o_zg : nullptr, p.Vp, p.Vp, st);
+        {
+            StageTimer tm(DPPO_STAGE_LOGITS_GEMM, st);
+            launch_mfma_logits(W, s.V, s.D, Hc, cv.n_cp, part, keep_z ? ws + p.o_zg : nullptr, p.Vp, p.Vp, st);
+        }
         launch_target_logit(1, Hc, W, y, cv.n_cp, s.D, zy, st);
         launch_combine_logprob(part, p.n_tiles, zy, cv, lse_c, logp_all, lse_all, st);
     } else {
@@ -206,6 +244,30 @@ int dppo_gather_f32(int64_t n, const int32_t* idx, const float* src, float* dst,
     if (!idx || !src || !dst) return fail(DPPO_ERR_INVALID_ARG, "a required array pointer is NULL");
     launch_gather_f32(n, idx, src, dst, (hipStream_t)stream);
     return check_launch("dppo_gather_f32");
+}
+
+int dppo_timing_enable(int on) {
+    std::lock_guard<std::mutex> lk(g_timing.mu);
+    g_timing.on = on != 0;
+    return DPPO_OK;
+}
+
+int dppo_timing_read(double* ms, int64_t* launches, int reset) {
+    if (!ms || !launches) return fail(DPPO_ERR_INVALID_ARG, "ms and launches must not be NULL");
+    std::lock_guard<std::mutex> lk(g_timing.mu);
+    for (int i = 0; i < DPPO_N_STAGES; ++i) { ms[i] = 0.0; launches[i] = 0; }
+    for (const auto& sp : g_timing.spans) {
+        float t = 0.0f;
+        hipError_t e = hipEventSynchronize(sp.b);
+        if (e == hipSuccess) e = hipEventElapsedTime(&t, sp.a, sp.b);
+        if (e != hipSuccess) return fail(DPPO_ERR_DEVICE, "stage timing: %s", hipGetErrorString(e));
+        if (sp.stage >= 0 && sp.stage < DPPO_N_STAGES) { ms[sp.stage] += (double)t; launches[sp.stage] += 1; }
+    }
+    if (reset) {
+        for (const auto& sp : g_timing.spans) { g_timing.pool.push_back(sp.a); g_timing.pool.push_back(sp.b); }
+        g_timing.spans.clear();
+    }
+    return DPPO_OK;
 }
 
 size_t dppo_workspace_bytes(const dppo_head_shape* shape, int want_backward) {
@@ -306,10 +368,13 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
         const float* lse_c = reinterpret_cast<const float*>(w + p.o_lse);
         void* G = w + p.o_zg;
         void* GT = w + p.o_gt;
-        if (recompute)
+        if (recompute) {
+            StageTimer tm(DPPO_STAGE_LOGITS_GEMM, st);
             launch_mfma_logits_grad(W, s.V, s.D, w + p.o_hc, cv.n_cp, y, lse_c, ta.c_chunk, G, GT, p.Vp, p.Vp, st);
-        else
+        } else {
+            StageTimer tm(DPPO_STAGE_GRAD_LOGITS, st);
             launch_grad_logits(s.dtype, G, GT, s.V, p.Vp, y, lse_c, ta.c_chunk, cv.n_cp, st);
+        }
 
         // dH rows of the chunk: G[n_c, Vp] * WT[D, Vp]^T, scattered to the loss rows of dH
         StoreSpec oh;
@@ -321,8 +386,14 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
         ow.C = dW; ow.ldc = s.D; ow.out_bf16 = 0; ow.accumulate = (first && !lp->accumulate_dW) ? 0 : 1;
         ow.row_map = nullptr; ow.row_base = 0;
         if (s.dtype == 1) {
-            launch_mfma_gemm(G, p.Vp, w + p.o_wt, p.Vp, cv.n_c, s.D, p.Vp, oh, st);
-            launch_mfma_gemm(GT, cv.n_cp, w + p.o_hct, cv.n_cp, s.V, s.D, cv.n_cp, ow, st);
+            {
+                StageTimer tm(DPPO_STAGE_DH_GEMM, st);
+                launch_mfma_gemm(G, p.Vp, w + p.o_wt, p.Vp, cv.n_c, s.D, p.Vp, oh, st);
+            }
+            {
+                StageTimer tm(DPPO_STAGE_DW_GEMM, st);
+                launch_mfma_gemm(GT, cv.n_cp, w + p.o_hct, cv.n_cp, s.V, s.D, cv.n_cp, ow, st);
+            }
         } else {
             launch_gemm_plain_f32(reinterpret_cast<const float*>(G), p.Vp, reinterpret_cast<const float*>(w + p.o_wt),
                                   p.Vp, cv.n_c, s.D, p.Vp, oh, st);

@@ -168,6 +168,9 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
 // ---------------------------------------------------------------------------------------
 // Epilogues
 // ---------------------------------------------------------------------------------------
+// Plain store of the accumulators. KIND 0 (dW): float output, overwrite or accumulate.
+// KIND 1 (dH): bf16 output, optional row scatter through row_map.
+template <int KIND>
 struct EpiStore {
     float* Cf; uint16_t* Cb; int64_t ldc; int accumulate; const int32_t* row_map; int64_t row_base;
 
@@ -179,15 +182,15 @@ struct EpiStore {
             for (int j = 0; j < 16; ++j) {
                 const int row = c.m0 + mi * 32 + acc_row(c.lane, j);
                 if (row >= c.M) continue;
-                const int64_t orow = row_map ? (int64_t)row_map[row_base + row] : (int64_t)row;
+                const int64_t orow = (KIND == 1 && row_map) ? (int64_t)row_map[row_base + row] : (int64_t)row;
 #pragma unroll
                 for (int ni = 0; ni < Cfg::NI; ++ni) {
                     const int col = c.n0 + ni * 32 + (c.lane & 31);
                     if (col >= c.N) continue;
                     const float v = acc[mi][ni][j];
                     const size_t idx = (size_t)orow * ldc + col;
-                    if (Cb) {
-                        __bf16 h = (__bf16)v;
+                    if (KIND == 1) {
+                        const __bf16 h = (__bf16)v;
                         Cb[idx] = __builtin_bit_cast(uint16_t, h);
                     } else {
                         Cf[idx] = accumulate ? Cf[idx] + v : v;
@@ -196,6 +199,8 @@ struct EpiStore {
             }
     }
 };
+typedef EpiStore<0> EpiStoreDW;
+typedef EpiStore<1> EpiStoreDH;
 
 constexpr float LOG2E = 1.4426950408889634f;
 
@@ -341,7 +346,8 @@ hipError_t allow_lds() {
 
 int mfma_setup() {
     static int status = [] {
-        hipError_t e = allow_lds<CfgBig, EpiStore>();
+        hipError_t e = allow_lds<CfgBig, EpiStoreDW>();
+        if (e == hipSuccess) e = allow_lds<CfgBig, EpiStoreDH>();
         if (e == hipSuccess) e = allow_lds<CfgBig, EpiLogits<true>>();
         if (e == hipSuccess) e = allow_lds<CfgBig, EpiLogits<false>>();
         if (e == hipSuccess) e = allow_lds<CfgBig, EpiLogitsGrad>();
@@ -373,10 +379,13 @@ void launch_mfma_logits_grad(const void* W, int32_t V, int32_t D, const void* Hc
 
 void launch_mfma_gemm(const void* A, int64_t lda, const void* B, int64_t ldb, int32_t M, int32_t N, int32_t K,
                       const StoreSpec& out, hipStream_t st) {
-    EpiStore e{out.out_bf16 ? nullptr : reinterpret_cast<float*>(out.C),
-               out.out_bf16 ? reinterpret_cast<uint16_t*>(out.C) : nullptr, out.ldc, out.accumulate,
-               out.row_map, out.row_base};
-    launch<CfgBig>(A, lda, B, ldb, M, N, K, e, st);
+    if (out.out_bf16) {
+        EpiStoreDH e{nullptr, reinterpret_cast<uint16_t*>(out.C), out.ldc, 0, out.row_map, out.row_base};
+        launch<CfgBig>(A, lda, B, ldb, M, N, K, e, st);
+    } else {
+        EpiStoreDW e{reinterpret_cast<float*>(out.C), nullptr, out.ldc, out.accumulate, nullptr, 0};
+        launch<CfgBig>(A, lda, B, ldb, M, N, K, e, st);
+    }
 }
 
 }  // namespace dppo
