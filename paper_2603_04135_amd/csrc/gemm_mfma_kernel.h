@@ -1,0 +1,401 @@
+// bf16 MFMA GEMM for gfx950, C[M,N] = A[M,K] * B[N,K]^T with both operands K-contiguous,
+// and the epilogues of the LM-head path fused onto its accumulators:
+//   * vocabulary GEMM (rows = vocabulary entries, columns = tokens): running max / sum-exp per
+//     token over the tile's vocabulary rows, so full logits never reach HBM; optionally the
+//     chunk's logits as fp16, or directly the softmax-gradient entries in bf16;
+//   * plain stores (fp32 / bf16, overwrite or accumulate, optional row scatter) for dH and dW.
+//
+// One workgroup owns a BM x BN output tile. K is streamed in slices of BK elements that go from
+// global memory straight into LDS (global_load_lds_dwordx4: no register staging, no ds_write),
+// STAGES slices deep. Each wavefront owns a (BM/WGM) x (BN/WGN) sub-tile of 32x32x16 MFMA blocks
+// and reads its operands one 16-wide k-step ahead into a second register set. The single barrier
+// per slice sits before the LAST k-step of the slice: the first operands of the next slice are
+// fetched, and the freed buffer is refilled, while the current slice still computes.
+//
+// LDS layout: a tile row is BK*2 bytes; its 16-byte chunks are XOR-swizzled so that the 16 lanes
+// a ds_read_b128 serves per cycle (16 consecutive tile rows, same k-chunk) fall into 16 different
+// 16-byte bank groups of the 64-bank LDS. A global_load_lds instruction always writes 64 lanes x
+// 16 bytes contiguously, so the swizzle is applied on the global-address side: each lane fetches
+// the chunk that belongs at the LDS position it will be written to.
+//
+// Workgroup ids are remapped so that the workgroups resident on one XCD (ids congruent mod 8)
+// cover a compact GROUP_M x n block of tiles and share operand panels in that XCD's L2.
+#pragma once
+#include "dppo_internal.h"
+
+namespace dppo {
+namespace mfma {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int NUM_XCD = 8;
+constexpr int GROUP_M = 8;        // tile rows per band of the tile walk
+
+struct TileCtx {
+    int M, N;          // logical output size
+    int tm, tn;        // tile coordinates
+    int m0, n0;        // first row / column of this wavefront's sub-tile
+    int bm0, bn0;      // first row / column of the workgroup tile
+    int wave_m, wave_n, lane, tid;
+    char* smem;
+};
+
+// Row of accumulator element j (0..15) of a 32x32 MFMA block, relative to the block.
+__device__ __forceinline__ int acc_row(int lane, int j) { return 8 * (j >> 2) + 4 * (lane >> 5) + (j & 3); }
+
+#define DPPO_GPTR(p) ((const void __attribute__((address_space(1)))*)(p))
+#define DPPO_LPTR(p) ((void __attribute__((address_space(3)))*)(p))
+
+// Waits until at most VM of this wavefront's global->LDS loads are outstanding and all its LDS
+// reads have returned, then joins the workgroup barrier. Raw s_barrier: a __syncthreads() fence
+// would also drain every outstanding load of the slices still in flight.
+template <int VM>
+__device__ __forceinline__ void wait_loads_then_barrier() {
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(VM) : "memory");
+}
+
+// XOR term of the LDS swizzle: logical 16-byte chunk kc of tile row `row` lives at physical chunk
+// kc ^ swz(row). Kind 3 (BK = 64, 8 chunks per row): (row & 7) ^ ((row >> 3) & 1); kinds 0..2:
+// (row >> kind) & (CPR - 1) (kind 2 is the conflict-free choice for BK = 32).
+template <int CPR, int SWZ> __device__ __forceinline__ int swz(int row) {
+    if (SWZ == 3) return ((row & 7) ^ ((row >> 3) & 1)) & (CPR - 1);
+    return (row >> SWZ) & (CPR - 1);
+}
+
+// BM x BN x BK tile, WGM x WGN wavefronts, STAGES slices in flight, swizzle kind SWZ; the loads of
+// a slice are issued over SPREAD consecutive k-steps; SCHED = 1 interleaves LDS reads and global
+// loads with the MFMAs of a k-step (scheduling hints only, no change of results).
+template <int BM_, int BN_, int BK_, int WGM_, int WGN_, int STAGES_, int SWZ_, int SPREAD_, int SCHED_>
+struct PipeCfg {
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WGM = WGM_, WGN = WGN_, STAGES = STAGES_;
+    static constexpr int SWZ = SWZ_, SPREAD = SPREAD_, SCHED = SCHED_;
+    static constexpr int NW = WGM * WGN, NT = NW * 64;
+    static constexpr int WTM = BM / WGM, WTN = BN / WGN;
+    static constexpr int MI = WTM / 32, NI = WTN / 32;
+    static constexpr int KK = BK / 16;
+    static constexpr int ROWB = BK * 2;
+    static constexpr int CPR = BK / 8;
+    static constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
+    static constexpr int A_LD = A_BYTES / 1024 / NW;
+    static constexpr int B_LD = B_BYTES / 1024 / NW;
+    static constexpr int LPS = A_LD + B_LD;
+    // loads of one slice are issued in SPREAD_STEPS consecutive k-steps, starting right after the barrier
+    static constexpr int SPREAD_STEPS = SPREAD < 1 ? 1 : SPREAD;
+    static_assert(SPREAD_STEPS <= KK, "spread");
+    static constexpr int LPSTEP = (LPS + SPREAD_STEPS - 1) / SPREAD_STEPS;
+    static_assert(LPS % SPREAD_STEPS == 0, "loads per step");
+    static_assert(BK == 32 || BK == 64, "BK");
+    static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile vs wavefront count");
+    static_assert((STAGES - 1) * LPS <= 63, "vmcnt range");
+    static_assert(KK % 2 == 0, "operand double buffer");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS");
+};
+
+template <class Cfg, class Epi>
+__global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __restrict__ A, int64_t lda,
+                                                          const uint16_t* __restrict__ B, int64_t ldb, int M,
+                                                          int N, int K, int tiles_m, int tiles_n, Epi epi) {
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    constexpr int MI = Cfg::MI, NI = Cfg::NI, KK = Cfg::KK, STAGES = Cfg::STAGES, LPS = Cfg::LPS;
+    constexpr int ROWB = Cfg::ROWB, CPR = Cfg::CPR, LPSTEP = Cfg::LPSTEP, SS = Cfg::SPREAD_STEPS;
+
+    const int total = tiles_m * tiles_n;
+    int logical;
+    {
+        const int bid = blockIdx.x;
+        const int xcd = bid % NUM_XCD, idx = bid / NUM_XCD;
+        const int per = total / NUM_XCD, rem = total % NUM_XCD;
+        logical = (xcd < rem) ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
+    }
+    int tm, tn;
+    {
+        const int band_sz = GROUP_M * tiles_n;
+        const int band = logical / band_sz, in_band = logical % band_sz;
+        const int first_m = band * GROUP_M;
+        const int gm = (tiles_m - first_m) < GROUP_M ? (tiles_m - first_m) : GROUP_M;
+        tm = first_m + in_band % gm;
+        tn = in_band / gm;
+    }
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wave_m = wave % Cfg::WGM, wave_n = wave / Cfg::WGM;
+    const int bm0 = tm * Cfg::BM, bn0 = tn * Cfg::BN;
+
+    // one pointer per load (A loads first, then B loads)
+    const uint16_t* pl[LPS];
+#pragma unroll
+    for (int i = 0; i < LPS; ++i) {
+        const bool isA = i < Cfg::A_LD;
+        const int ii = isA ? i : i - Cfg::A_LD;
+        const int ci = (ii * Cfg::NW + wave) * 64 + lane;
+        const int row = ci / CPR, pc = ci % CPR;
+        const int kc = pc ^ swz<CPR, Cfg::SWZ>(row);
+        int r = (isA ? bm0 : bn0) + row;
+        const int lim = isA ? M : N;
+        r = r < lim ? r : lim - 1;
+        pl[i] = (isA ? A : B) + (size_t)r * (isA ? lda : ldb) + kc * 8;
+    }
+    // issues loads [first, first+count) of slice kt into buffer buf
+    auto issue_loads = [&](int buf, int kt, int first, int count) {
+        char* dst = smem + buf * Cfg::STAGE_BYTES + wave * 1024;
+        const size_t koff = (size_t)kt * Cfg::BK;
+#pragma unroll
+        for (int i = 0; i < LPS; ++i) {
+            if (i < first || i >= first + count) continue;
+            const bool isA = i < Cfg::A_LD;
+            const int ii = isA ? i : i - Cfg::A_LD;
+            __builtin_amdgcn_global_load_lds(DPPO_GPTR(pl[i] + koff),
+                                             DPPO_LPTR(dst + (isA ? 0 : Cfg::A_BYTES) + ii * Cfg::NW * 1024), 16, 0, 0);
+        }
+    };
+
+    const int frag_row = lane & 31, frag_half = lane >> 5;
+    const int sw = swz<CPR, Cfg::SWZ>(frag_row);
+    const int a_base = (wave_m * Cfg::WTM + frag_row) * ROWB;
+    const int b_base = Cfg::A_BYTES + (wave_n * Cfg::WTN + frag_row) * ROWB;
+    bf16x8 af[2][MI], bfr[2][NI];
+    auto read_frags = [&](int set, int buf, int kk) {
+        const char* st = smem + buf * Cfg::STAGE_BYTES;
+        const int kc_off = ((kk * 2 + frag_half) ^ sw) << 4;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+            af[set][mi] = *reinterpret_cast<const bf16x8*>(st + a_base + mi * 32 * ROWB + kc_off);
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+            bfr[set][ni] = *reinterpret_cast<const bf16x8*>(st + b_base + ni * 32 * ROWB + kc_off);
+    };
+
+    f32x16 acc[MI][NI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc[mi][ni][j] = 0.0f;
+
+    const int KT = K / Cfg::BK;
+#pragma unroll
+    for (int s = 0; s < STAGES; ++s)
+        if (s < KT) issue_loads(s, s, 0, LPS);
+    if (KT >= STAGES) wait_loads_then_barrier<(STAGES - 1) * LPS>();
+    else wait_loads_then_barrier<0>();
+    read_frags(0, 0, 0);
+
+    // Slice kt+STAGES is fetched into the buffer of slice kt. That buffer is released by the barrier
+    // at the last k-step of slice kt; its loads are issued in the SS k-steps that follow (the last
+    // step of slice kt and the first SS-1 steps of slice kt+1).
+    int buf = 0;
+    for (int kt = 0; kt < KT; ++kt) {
+        const int nbuf = (buf + 1 == STAGES) ? 0 : buf + 1;
+        const int pbuf = (buf == 0) ? STAGES - 1 : buf - 1;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            const int cur = kk & 1, nxt = cur ^ 1;
+            if (kk == KK - 1) {
+                if (kt + 1 < KT) {
+                    // outstanding loads issued after slice kt+1: slices kt+2 .. kt+STAGES-1 complete, plus
+                    // nothing of slice kt+STAGES yet (its first part is issued below)
+                    if (kt + STAGES <= KT) wait_loads_then_barrier<(STAGES - 2) * LPS>();
+                    else wait_loads_then_barrier<0>();
+                    if (kt + STAGES < KT) issue_loads(buf, kt + STAGES, 0, LPSTEP);
+                    read_frags(nxt, nbuf, 0);
+                }
+            } else {
+                if (SS > 1 && kk + 1 < SS && kt >= 1 && kt - 1 + STAGES < KT)
+                    issue_loads(pbuf, kt - 1 + STAGES, (kk + 1) * LPSTEP, LPSTEP);
+                read_frags(nxt, buf, kk + 1);
+            }
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][mi], bfr[cur][ni], acc[mi][ni], 0, 0, 0);
+            if (Cfg::SCHED == 1) {
+                // interleave: one LDS read per two MFMAs, one global load per four MFMAs
+#pragma unroll
+                for (int q = 0; q < (MI * NI) / 2; ++q) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
+                    if ((q & 1) == 0) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // VMEM read
+                    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);   // MFMA
+                }
+            }
+        }
+        buf = nbuf;
+    }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+
+    TileCtx c;
+    c.M = M; c.N = N; c.tm = tm; c.tn = tn;
+    c.bm0 = bm0; c.bn0 = bn0;
+    c.m0 = bm0 + wave_m * Cfg::WTM; c.n0 = bn0 + wave_n * Cfg::WTN;
+    c.wave_m = wave_m; c.wave_n = wave_n; c.lane = lane; c.tid = tid; c.smem = smem;
+    epi.template run<Cfg>(acc, c);
+}
+
+// ---------------------------------------------------------------------------------------
+// Epilogues
+// ---------------------------------------------------------------------------------------
+// Plain store of the accumulators. KIND 0 (dW): float output, overwrite or accumulate.
+// KIND 1 (dH): bf16 output, optional row scatter through row_map.
+template <int KIND>
+struct EpiStore {
+    float* Cf; uint16_t* Cb; int64_t ldc; int accumulate; const int32_t* row_map; int64_t row_base;
+
+    template <class Cfg>
+    __device__ __forceinline__ void run(f32x16 (&acc)[Cfg::MI][Cfg::NI], const TileCtx& c) const {
+#pragma unroll
+        for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const int row = c.m0 + mi * 32 + acc_row(c.lane, j);
+                if (row >= c.M) continue;
+                const int64_t orow = (KIND == 1 && row_map) ? (int64_t)row_map[row_base + row] : (int64_t)row;
+#pragma unroll
+                for (int ni = 0; ni < Cfg::NI; ++ni) {
+                    const int col = c.n0 + ni * 32 + (c.lane & 31);
+                    if (col >= c.N) continue;
+                    const float v = acc[mi][ni][j];
+                    const size_t idx = (size_t)orow * ldc + col;
+                    if (KIND == 1) {
+                        const __bf16 h = (__bf16)v;
+                        Cb[idx] = __builtin_bit_cast(uint16_t, h);
+                    } else {
+                        Cf[idx] = accumulate ? Cf[idx] + v : v;
+                    }
+                }
+            }
+    }
+};
+typedef EpiStore<0> EpiStoreDW;
+typedef EpiStore<1> EpiStoreDH;
+
+constexpr float LOG2E = 1.4426950408889634f;
+
+// Rows = vocabulary entries, columns = tokens.
+template <bool STORE_Z>
+struct EpiLogits {
+    float2* part; int64_t n_cp;    // part[tile_m * n_cp + token]
+    _Float16* Z16; int64_t ldz; int Vp;
+
+    template <class Cfg>
+    __device__ __forceinline__ void run(f32x16 (&acc)[Cfg::MI][Cfg::NI], const TileCtx& c) const {
+        constexpr int MI = Cfg::MI, NI = Cfg::NI;
+        const float NEG_INF = -__builtin_inff();
+        float mx[NI], sm[NI];
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+            float m = NEG_INF;
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const int row = c.m0 + mi * 32 + acc_row(c.lane, j);
+                    const float v = row < c.M ? acc[mi][ni][j] : NEG_INF;
+                    m = fmaxf(m, v);
+                }
+            m = fmaxf(m, __shfl_xor(m, 32, 64));
+            const float mref = (m == NEG_INF) ? 0.0f : m;
+            float s = 0.0f;
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const int row = c.m0 + mi * 32 + acc_row(c.lane, j);
+                    const float e = __builtin_amdgcn_exp2f((acc[mi][ni][j] - mref) * LOG2E);
+                    s += row < c.M ? e : 0.0f;
+                }
+            s += __shfl_xor(s, 32, 64);
+            mx[ni] = m; sm[ni] = s;
+        }
+        if (STORE_Z) {
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) {
+                const int64_t col = c.n0 + ni * 32 + (c.lane & 31);
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int v0 = c.m0 + mi * 32 + 8 * g + 4 * (c.lane >> 5);
+                        if (v0 < Vp) {
+                            f16x4 h;
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) {
+                                float z = acc[mi][ni][4 * g + q];
+                                z = fminf(fmaxf(z, -65504.0f), 65504.0f);
+                                h[q] = (_Float16)z;
+                            }
+                            *reinterpret_cast<f16x4*>(Z16 + col * ldz + v0) = h;
+                        }
+                    }
+            }
+        }
+        // combine the WGM wavefronts that cover the same tokens
+        __syncthreads();
+        float2* red = reinterpret_cast<float2*>(c.smem);
+        if (c.lane < 32) {
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+                red[c.wave_m * Cfg::BN + c.wave_n * Cfg::WTN + ni * 32 + c.lane] = make_float2(mx[ni], sm[ni]);
+        }
+        __syncthreads();
+        for (int t = c.tid; t < Cfg::BN; t += Cfg::NT) {
+            float m = NEG_INF;
+#pragma unroll
+            for (int w = 0; w < Cfg::WGM; ++w) m = fmaxf(m, red[w * Cfg::BN + t].x);
+            float s = 0.0f;
+#pragma unroll
+            for (int w = 0; w < Cfg::WGM; ++w) {
+                const float2 r = red[w * Cfg::BN + t];
+                s += (r.x == NEG_INF) ? 0.0f : r.y * __builtin_amdgcn_exp2f((r.x - m) * LOG2E);
+            }
+            const int64_t tok = c.bn0 + t;
+            if (tok < n_cp) part[(int64_t)c.tm * n_cp + tok] = make_float2(m, s);
+        }
+    }
+};
+
+// Rows = vocabulary entries, columns = tokens: softmax-gradient entries straight from the logits.
+struct EpiLogitsGrad {
+    const int32_t* y; const float* lse; const float* cvec;
+    uint16_t* G; uint16_t* GT; int64_t ldg; int64_t n_cp; int V, Vp;
+
+    template <class Cfg>
+    __device__ __forceinline__ void run(f32x16 (&acc)[Cfg::MI][Cfg::NI], const TileCtx& c) const {
+#pragma unroll
+        for (int ni = 0; ni < Cfg::NI; ++ni) {
+            const int64_t col = c.n0 + ni * 32 + (c.lane & 31);
+            const bool col_ok = col < n_cp;
+            const int yt = col_ok ? y[col] : -1;
+            const float l = col_ok ? lse[col] : 0.0f;
+            const float cn = col_ok ? cvec[col] : 0.0f;
+#pragma unroll
+            for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int v0 = c.m0 + mi * 32 + 8 * g + 4 * (c.lane >> 5);
+                    if (v0 < Vp && col_ok) {
+                        bf16x4 h;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const int v = v0 + q;
+                            const float p = __builtin_amdgcn_exp2f((acc[mi][ni][4 * g + q] - l) * LOG2E);
+                            float gv = cn * ((v == yt ? 1.0f : 0.0f) - p);
+                            gv = v < V ? gv : 0.0f;
+                            const __bf16 b = (__bf16)gv;   // scalar copy: reading h[q] back right after writing it miscompiles
+                            h[q] = b;
+                            GT[(int64_t)v * n_cp + col] = __builtin_bit_cast(uint16_t, b);
+                        }
+                        *reinterpret_cast<bf16x4*>(G + col * ldg + v0) = h;
+                    }
+                }
+        }
+    }
+};
+
+}  // namespace mfma
+}  // namespace dppo
