@@ -74,6 +74,8 @@ def main() -> int:
     ap.add_argument("--workload", default="qwen3_4b")
     ap.add_argument("--cpu-sample", type=int, default=2048, help="loss tokens the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--recompute", action="store_true", help="recompute the logits in the backward")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (reference point for HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no sharding, no collectives)"
@@ -171,6 +173,13 @@ def main() -> int:
                     "avg_launch_ms": avg_ms, "launches_per_step": launches_per_step}
     stage_ms = {k: v[0] / args.steps for k, v in stages.items()}
     mfu = 6.0 * wl.D * wl.V * N / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     cpu = None
     if args.cpu_sample > 0:
