@@ -5,8 +5,9 @@ namespace dppo {
 namespace {
 using namespace mfma;
 
-// 256x256x64 tile, 2x4 wavefronts (128x64 each), 2 slices in flight, loads spread over 2 k-steps.
-typedef PipeCfg<256, 256, 64, 2, 4, 2, 3, 2, 1> CfgBig;
+// 256x256x64 tile, 2x4 wavefronts (128x64 each), 2 slices in flight, loads spread over 2 k-steps,
+// bands of 4 tile rows.
+typedef PipeCfg<256, 256, 64, 2, 4, 2, 3, 2, 4> CfgBig;
 
 template <class Cfg, class Epi>
 void launch(const void* A, int64_t lda, const void* B, int64_t ldb, int M, int N, int K, const Epi& epi,

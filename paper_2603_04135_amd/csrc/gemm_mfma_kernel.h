@@ -21,6 +21,8 @@
 // Workgroup ids are remapped so that the workgroups resident on one XCD (ids congruent mod 8)
 // cover a compact GROUP_M x n block of tiles and share operand panels in that XCD's L2.
 #pragma once
+#include <type_traits>
+
 #include "dppo_internal.h"
 
 namespace dppo {
@@ -33,7 +35,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int NUM_XCD = 8;
-constexpr int GROUP_M = 8;        // tile rows per band of the tile walk
 
 struct TileCtx {
     int M, N;          // logical output size
@@ -67,12 +68,13 @@ template <int CPR, int SWZ> __device__ __forceinline__ int swz(int row) {
 }
 
 // BM x BN x BK tile, WGM x WGN wavefronts, STAGES slices in flight, swizzle kind SWZ; the loads of
-// a slice are issued over SPREAD consecutive k-steps; SCHED = 1 interleaves LDS reads and global
-// loads with the MFMAs of a k-step (scheduling hints only, no change of results).
-template <int BM_, int BN_, int BK_, int WGM_, int WGN_, int STAGES_, int SWZ_, int SPREAD_, int SCHED_>
+// a slice are issued over SPREAD consecutive k-steps; GROUP_M tile rows form one band of the tile
+// walk.
+template <int BM_, int BN_, int BK_, int WGM_, int WGN_, int STAGES_, int SWZ_, int SPREAD_, int GROUP_M_>
 struct PipeCfg {
+    static constexpr int GROUP_M = GROUP_M_;   // tile rows per band of the tile walk
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WGM = WGM_, WGN = WGN_, STAGES = STAGES_;
-    static constexpr int SWZ = SWZ_, SPREAD = SPREAD_, SCHED = SCHED_;
+    static constexpr int SWZ = SWZ_, SPREAD = SPREAD_;
     static constexpr int NW = WGM * WGN, NT = NW * 64;
     static constexpr int WTM = BM / WGM, WTN = BN / WGN;
     static constexpr int MI = WTM / 32, NI = WTN / 32;
@@ -95,6 +97,7 @@ struct PipeCfg {
     static_assert((STAGES - 1) * LPS <= 63, "vmcnt range");
     static_assert(KK % 2 == 0, "operand double buffer");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS");
+    static_assert(MI + NI <= MI * NI && LPSTEP <= MI * NI, "one read / load slot per MFMA of a k-step");
 };
 
 template <class Cfg, class Epi>
@@ -115,6 +118,7 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
     }
     int tm, tn;
     {
+        constexpr int GROUP_M = Cfg::GROUP_M;
         const int band_sz = GROUP_M * tiles_n;
         const int band = logical / band_sz, in_band = logical % band_sz;
         const int first_m = band * GROUP_M;
@@ -122,7 +126,8 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
         tm = first_m + in_band % gm;
         tn = in_band / gm;
     }
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps LDS targets in SGPRs
     const int wave_m = wave % Cfg::WGM, wave_n = wave / Cfg::WGM;
     const int bm0 = tm * Cfg::BM, bn0 = tn * Cfg::BN;
 
@@ -170,6 +175,13 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
             bfr[set][ni] = *reinterpret_cast<const bf16x8*>(st + b_base + ni * 32 * ROWB + kc_off);
     };
 
+    auto read_one = [&](int set, int buf, int kk, bool isA, int idx) {
+        const char* st = smem + buf * Cfg::STAGE_BYTES;
+        const int kc_off = ((kk * 2 + frag_half) ^ sw) << 4;
+        if (isA) af[set][idx] = *reinterpret_cast<const bf16x8*>(st + a_base + idx * 32 * ROWB + kc_off);
+        else bfr[set][idx] = *reinterpret_cast<const bf16x8*>(st + b_base + idx * 32 * ROWB + kc_off);
+    };
+
     f32x16 acc[MI][NI];
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi)
@@ -189,44 +201,59 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
     // Slice kt+STAGES is fetched into the buffer of slice kt. That buffer is released by the barrier
     // at the last k-step of slice kt; its loads are issued in the SS k-steps that follow (the last
     // step of slice kt and the first SS-1 steps of slice kt+1).
+    // One slice = KK k-steps. STEADY iterations (1 <= kt, kt + STAGES < KT) have every condition
+    // resolved at compile time, so the whole slice is straight-line code.
     int buf = 0;
-    for (int kt = 0; kt < KT; ++kt) {
+    auto slice = [&](int kt, auto steady_tag) {
+        constexpr bool STEADY = decltype(steady_tag)::value;
         const int nbuf = (buf + 1 == STAGES) ? 0 : buf + 1;
         const int pbuf = (buf == 0) ? STAGES - 1 : buf - 1;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
             const int cur = kk & 1, nxt = cur ^ 1;
+            bool loads_here = false, reads_here = false;
+            int load_buf = 0, load_kt = 0, load_first = 0, read_buf = 0, read_kk = 0;
             if (kk == KK - 1) {
-                if (kt + 1 < KT) {
-                    // outstanding loads issued after slice kt+1: slices kt+2 .. kt+STAGES-1 complete, plus
-                    // nothing of slice kt+STAGES yet (its first part is issued below)
-                    if (kt + STAGES <= KT) wait_loads_then_barrier<(STAGES - 2) * LPS>();
+                if (STEADY || kt + 1 < KT) {
+                    // loads issued after slice kt+1: slices kt+2 .. kt+STAGES-1 (complete); the first
+                    // part of slice kt+STAGES is issued below
+                    if (STEADY || kt + STAGES <= KT) wait_loads_then_barrier<(STAGES - 2) * LPS>();
                     else wait_loads_then_barrier<0>();
-                    if (kt + STAGES < KT) issue_loads(buf, kt + STAGES, 0, LPSTEP);
-                    read_frags(nxt, nbuf, 0);
+                    if (STEADY || kt + STAGES < KT) { load_buf = buf; load_kt = kt + STAGES; load_first = 0; loads_here = true; }
+                    read_buf = nbuf; read_kk = 0; reads_here = true;
                 }
             } else {
-                if (SS > 1 && kk + 1 < SS && kt >= 1 && kt - 1 + STAGES < KT)
-                    issue_loads(pbuf, kt - 1 + STAGES, (kk + 1) * LPSTEP, LPSTEP);
-                read_frags(nxt, buf, kk + 1);
+                if (SS > 1 && kk + 1 < SS && (STEADY || (kt >= 1 && kt - 1 + STAGES < KT))) {
+                    load_buf = pbuf; load_kt = kt - 1 + STAGES; load_first = (kk + 1) * LPSTEP; loads_here = true;
+                }
+                read_buf = buf; read_kk = kk + 1; reads_here = true;
             }
+            {
+                // Instruction order of a k-step, pinned by scheduling barriers (left to itself the
+                // compiler sinks the reads next to their use and exposes the LDS latency):
+                // MFMA q, then operand read q of the next k-step (A0 B0 B1 .. then the remaining A
+                // blocks) and one global load.
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni)
+                for (int q = 0; q < MI * NI; ++q) {
+                    const int mi = q / NI, ni = q % NI;
                     acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][mi], bfr[cur][ni], acc[mi][ni], 0, 0, 0);
-            if (Cfg::SCHED == 1) {
-                // interleave: one LDS read per two MFMAs, one global load per four MFMAs
-#pragma unroll
-                for (int q = 0; q < (MI * NI) / 2; ++q) {
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
-                    if ((q & 1) == 0) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // VMEM read
-                    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);   // MFMA
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (reads_here && q < MI + NI) {
+                        const int which = q == 0 ? 0 : (q <= NI ? -q : q - NI);   // >= 0: A block, < 0: B block -which-1
+                        if (which >= 0) read_one(nxt, read_buf, read_kk, true, which);
+                        else read_one(nxt, read_buf, read_kk, false, -which - 1);
+                    }
+                    if (loads_here && q < LPSTEP) issue_loads(load_buf, load_kt, load_first + q, 1);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
         }
         buf = nbuf;
-    }
+    };
+    int kt = 0;
+    if (KT > 0) { slice(0, std::false_type{}); kt = 1; }
+    for (; kt + STAGES < KT; ++kt) slice(kt, std::true_type{});
+    for (; kt < KT; ++kt) slice(kt, std::false_type{});
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
     TileCtx c;
