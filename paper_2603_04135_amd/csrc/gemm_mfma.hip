@@ -9,11 +9,19 @@ using namespace mfma;
 // bands of 4 tile rows.
 typedef PipeCfg<256, 256, 64, 2, 4, 2, 3, 2, 4> CfgBig;
 
+// Dynamic LDS of a kernel: the operand slices, or the epilogue's staging area if that is larger.
+template <class Cfg, class Epi>
+constexpr int lds_request() {
+    constexpr int e = Epi::template lds_bytes<Cfg>();
+    static_assert(e <= 160 * 1024, "epilogue LDS");
+    return Cfg::LDS_BYTES > e ? Cfg::LDS_BYTES : e;
+}
+
 template <class Cfg, class Epi>
 void launch(const void* A, int64_t lda, const void* B, int64_t ldb, int M, int N, int K, const Epi& epi,
             hipStream_t st) {
     const int tiles_m = (int)ceil_div(M, Cfg::BM), tiles_n = (int)ceil_div(N, Cfg::BN);
-    gemm_nt_kernel<Cfg, Epi><<<dim3(tiles_m * tiles_n), dim3(Cfg::NT), Cfg::LDS_BYTES, st>>>(
+    gemm_nt_kernel<Cfg, Epi><<<dim3(tiles_m * tiles_n), dim3(Cfg::NT), lds_request<Cfg, Epi>(), st>>>(
         reinterpret_cast<const uint16_t*>(A), lda, reinterpret_cast<const uint16_t*>(B), ldb, M, N, K, tiles_m,
         tiles_n, epi);
 }
@@ -21,7 +29,7 @@ void launch(const void* A, int64_t lda, const void* B, int64_t ldb, int M, int N
 template <class Cfg, class Epi>
 hipError_t allow_lds() {
     return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_kernel<Cfg, Epi>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
+                               hipFuncAttributeMaxDynamicSharedMemorySize, lds_request<Cfg, Epi>());
 }
 
 }  // namespace

@@ -297,6 +297,9 @@ struct EpiStore {
                 }
             }
     }
+
+    template <class Cfg>
+    static constexpr int lds_bytes() { return 0; }
 };
 typedef EpiStore<0> EpiStoreDW;
 typedef EpiStore<1> EpiStoreDH;
@@ -339,37 +342,51 @@ struct EpiLogits {
             s += __shfl_xor(s, 32, 64);
             mx[ni] = m; sm[ni] = s;
         }
+        // LDS (free after the main loop's closing barrier): the tile's logits as fp16, laid out
+        // [token][vocabulary row] so that they leave as 16-byte stores of whole 512-byte row pieces,
+        // then the per-wavefront (max, sum) pairs of the WGM wavefronts that share a token.
+        constexpr int ZPITCH = Cfg::BM * 2 + 16;      // bytes per token row; +16 staggers the banks
+        float2* red = reinterpret_cast<float2*>(c.smem + (STORE_Z ? Cfg::BN * ZPITCH : 0));
         if (STORE_Z) {
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni) {
-                const int64_t col = c.n0 + ni * 32 + (c.lane & 31);
+                const int tok = c.wave_n * Cfg::WTN + ni * 32 + (c.lane & 31);
 #pragma unroll
                 for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
-                        const int v0 = c.m0 + mi * 32 + 8 * g + 4 * (c.lane >> 5);
-                        if (v0 < Vp) {
-                            f16x4 h;
+                        const int vloc = c.wave_m * Cfg::WTM + mi * 32 + 8 * g + 4 * (c.lane >> 5);
+                        f16x4 h;
 #pragma unroll
-                            for (int q = 0; q < 4; ++q) {
-                                float z = acc[mi][ni][4 * g + q];
-                                z = fminf(fmaxf(z, -65504.0f), 65504.0f);
-                                h[q] = (_Float16)z;
-                            }
-                            *reinterpret_cast<f16x4*>(Z16 + col * ldz + v0) = h;
+                        for (int q = 0; q < 4; ++q) {
+                            float z = acc[mi][ni][4 * g + q];
+                            z = fminf(fmaxf(z, -65504.0f), 65504.0f);
+                            h[q] = (_Float16)z;
                         }
+                        *reinterpret_cast<f16x4*>(c.smem + tok * ZPITCH + vloc * 2) = h;
                     }
             }
         }
-        // combine the WGM wavefronts that cover the same tokens
-        __syncthreads();
-        float2* red = reinterpret_cast<float2*>(c.smem);
         if (c.lane < 32) {
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni)
                 red[c.wave_m * Cfg::BN + c.wave_n * Cfg::WTN + ni * 32 + c.lane] = make_float2(mx[ni], sm[ni]);
         }
         __syncthreads();
+        if (STORE_Z) {
+            // 32 lanes x 16 bytes = one 512-byte token row of the tile; two rows per instruction
+            constexpr int CH = Cfg::BM / 8;                     // 16-byte chunks per row
+            constexpr int ROWS_PER_PASS = Cfg::NT / CH;
+            const int ch = c.tid % CH;
+            const int v0 = c.bm0 + ch * 8;
+            if (v0 < Vp) {
+#pragma unroll 4
+                for (int r = c.tid / CH; r < Cfg::BN; r += ROWS_PER_PASS) {
+                    const u32x4 val = *reinterpret_cast<const u32x4*>(c.smem + r * ZPITCH + ch * 16);
+                    *reinterpret_cast<u32x4*>(Z16 + (int64_t)(c.bn0 + r) * ldz + v0) = val;
+                }
+            }
+        }
         for (int t = c.tid; t < Cfg::BN; t += Cfg::NT) {
             float m = NEG_INF;
 #pragma unroll
@@ -383,6 +400,11 @@ struct EpiLogits {
             const int64_t tok = c.bn0 + t;
             if (tok < n_cp) part[(int64_t)c.tm * n_cp + tok] = make_float2(m, s);
         }
+    }
+
+    template <class Cfg>
+    static constexpr int lds_bytes() {
+        return (STORE_Z ? Cfg::BN * (Cfg::BM * 2 + 16) : 0) + Cfg::WGM * Cfg::BN * 8;
     }
 };
 
@@ -422,6 +444,9 @@ struct EpiLogitsGrad {
                 }
         }
     }
+
+    template <class Cfg>
+    static constexpr int lds_bytes() { return 0; }
 };
 
 }  // namespace mfma
