@@ -1,0 +1,125 @@
+"""Whole-batch runs at the workloads' full sizes, in the configuration bench.py times
+(select -> pack -> gather -> loss forward+backward through the C ABI, recommended workspace).
+
+The oracle cannot run these batches whole, so it checks what it can compute one by one --
+log-probs, dH rows and per-sequence losses of sampled tokens / sequences, each from the same
+inputs by its own arithmetic -- and the rest is held to properties that hold at any size."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as WL
+from oracle import dppo_oracle as O
+from harness import to_np64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2603_04135_amd as P
+    P.load()
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return P
+
+
+def _oracle_rows(H_rows64, W64, y):
+    """logits, lse and log-prob of a few rows (fp64)."""
+    Z = H_rows64 @ W64.T
+    m = Z.max(axis=1)
+    lse = m + np.log(np.exp(Z - m[:, None]).sum(axis=1))
+    return Z, lse, Z[np.arange(len(y)), y] - lse
+
+
+@pytest.mark.parametrize("name", ["small", "qwen3_4b", "qwen3_8b", "stress"])
+def test_whole_batch_sampled_against_oracle(lib, name):
+    P = lib
+    rb = WL.make_rollout(name)
+    wl = rb.wl
+    # selection and packing on the GPU, bit-exact against the oracle
+    sel = P.dppo_select(rb.rewards, rb.hist, rb.u_prompt, rb.u_comp, wl.r_q, wl.r_o, device=DEV)
+    pk = P.dppo_pack(rb.item_prompt_len, rb.item_comp_len, sel["keep_comp"].reshape(-1), wl.capacity, wl.n_win,
+                     device=DEV)
+    o_sel = O.select(rb.rewards, rb.hist, rb.u_prompt, rb.u_comp, wl.r_q, wl.r_o)
+    o_pk = O.pack(rb.item_prompt_len, rb.item_comp_len, o_sel["keep_comp"].reshape(-1), wl.capacity, wl.n_win)
+    assert np.array_equal(sel["keep_comp"].cpu().numpy(), o_sel["keep_comp"])
+    for k in ("order", "row_ptr", "cu_seqlens", "loss_cu", "loss_pos"):
+        assert np.array_equal(pk[k].cpu().numpy(), o_pk[k]), k
+    T, N, S = pk["T"], pk["N"], pk["S"]
+    seed = rb.seed
+    H = WL.make_hidden(wl, T, seed, DEV)
+    W = WL.make_vocab_matrix(wl, seed, DEV)
+    ids_np = WL.make_ids(wl, T, seed)
+    ids = torch.as_tensor(ids_np, device=DEV)
+    seq_adv = P.dppo_gather_f32(pk["order"], sel["adv"])
+    seq_coef = P.dppo_gather_f32(pk["order"], sel["coef"])
+
+    # old / reference log-probs: seeded noise around a seeded synthetic base (inputs, not results)
+    rng = np.random.default_rng([seed, 77])
+    base = (-np.log(wl.V) - rng.random(N)).astype(np.float32)
+    old_np = WL.perturb_logp(base, 0.3, seed, 0)
+    ref_np = WL.perturb_logp(base, 0.3, seed, 1)
+    logp_old = torch.as_tensor(old_np, device=DEV)
+    logp_ref = torch.as_tensor(ref_np, device=DEV)
+
+    out = P.dppo_loss_fwd_bwd(H, W, ids, pk["loss_pos"], pk["loss_cu"], seq_adv, seq_coef, logp_old, logp_ref,
+                              wl.clip_eps, wl.clip_eps, wl.kl_beta)
+    torch.cuda.synchronize()
+    logp_gpu = out["logp"].cpu().numpy()
+    seq_loss_gpu = out["seq_loss"].cpu().numpy().astype(np.float64)
+    loss_gpu = float(out["loss"].item())
+    assert np.isfinite(loss_gpu) and np.isfinite(logp_gpu).all()
+
+    W64 = to_np64(W)
+    loss_pos, loss_cu = o_pk["loss_pos"], o_pk["loss_cu"]
+    adv_s = o_sel["adv"].reshape(-1)[o_pk["order"]].astype(np.float32)
+    coef_s = o_sel["coef"].reshape(-1)[o_pk["order"]].astype(np.float32)
+
+    # (a) sampled tokens: first / last token, chunk borders, random ones
+    pick = np.unique(np.concatenate([[0, 1, N - 1, N // 2, min(N - 1, 32255), min(N - 1, 32256)],
+                                     rng.integers(0, N, size=26)]))
+    rows = loss_pos[pick]
+    y = ids_np[rows + 1]
+    Hs = to_np64(H[torch.as_tensor(rows, device=DEV).long()])
+    Z, lse, logp_o = _oracle_rows(Hs, W64, y)
+    assert np.abs(logp_gpu[pick] - logp_o).max() <= 2e-3
+
+    # (b) dH rows of those tokens: c_n (W[y] - p W), c_n from the oracle's token terms
+    s_of = np.searchsorted(loss_cu, pick, side="right") - 1
+    C = (loss_cu[s_of + 1] - loss_cu[s_of]).astype(np.float64)
+    ell, g, kl, away = O.token_terms(logp_o, old_np[pick], ref_np[pick], adv_s[s_of].astype(np.float64),
+                                     wl.clip_eps, wl.clip_eps, wl.kl_beta)
+    c = coef_s[s_of].astype(np.float64) / C * g
+    Pm = np.exp(Z - lse[:, None])
+    dH_o = c[:, None] * (W64[y] - Pm @ W64)
+    dH_g = to_np64(out["dH"][torch.as_tensor(rows, device=DEV).long()])
+    nz = np.abs(c) > 0
+    assert nz.sum() >= 8 and away.any() and (~away).any()
+    num = np.linalg.norm(dH_g[nz] - dH_o[nz])
+    assert num / np.linalg.norm(dH_o[nz]) <= 1e-2
+    assert not dH_g[~nz].any()
+
+    # (c) per-sequence loss of the two shortest sequences, every token by the oracle
+    lens = np.diff(loss_cu)
+    for s in np.argsort(lens, kind="stable")[:2]:
+        a, b = int(loss_cu[s]), int(loss_cu[s + 1])
+        r = loss_pos[a:b]
+        _, _, lp = _oracle_rows(to_np64(H[torch.as_tensor(r, device=DEV).long()]), W64, ids_np[r + 1])
+        el, _, _, _ = O.token_terms(lp, old_np[a:b], ref_np[a:b], float(adv_s[s]), wl.clip_eps, wl.clip_eps, wl.kl_beta)
+        assert abs(seq_loss_gpu[s] - el.mean()) <= 1e-3 * abs(el.mean()) + 2e-3
+
+    # (d) properties that hold at any size
+    total = float(np.sum(coef_s.astype(np.float64) * seq_loss_gpu))
+    scale = float(np.abs(coef_s.astype(np.float64) * seq_loss_gpu).sum())
+    assert abs(loss_gpu - total) <= 1e-5 * scale                       # loss = sum_s coef_s * seq_loss_s
+    mask = torch.ones(T, dtype=torch.bool, device=DEV)
+    mask[pk["loss_pos"].long()] = False
+    assert not bool(out["dH"][mask].any())                              # rows that predict nothing
+    dW = out["dW"]
+    col = dW.sum(dim=0, dtype=torch.float64)                            # softmax gradients sum to zero over V
+    assert float(col.abs().max()) <= 2e-2 * float(dW.abs().sum(dim=0, dtype=torch.float64).max())
+    stats = out["stats"].cpu().numpy()
+    assert stats[2] == N and 0.0 < stats[1] < 1.0 and stats[0] > 0.0
+    del out, H, W, dW
+    torch.cuda.empty_cache()
