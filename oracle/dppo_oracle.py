@@ -89,8 +89,20 @@ def prompt_candidates(hist, bottom_frac: float = 0.5) -> np.ndarray:
 # ----------------------------------------------------------------------------
 # Sec. 4.2: pruning policies (Eq. 14-17), realised masks, rescaling (Eq. 18)
 # ----------------------------------------------------------------------------
+def fixed_prune_count(r: float, n: int) -> int:
+    """Number pruned from a candidate set of n in the fixed-count form (App. A; Alg. 1:
+    floor(r * n)). r arrives as float32 (relative error 6e-8), so the product is scaled by
+    1 + 1e-6 before the floor: 0.9f * 10 gives 9 and 0.7f * 100 gives 70. At least one
+    candidate always survives."""
+    if n <= 0:
+        return 0
+    m = int(math.floor(float(np.float32(r)) * n * (1.0 + 1e-6)))
+    return max(0, min(m, n - 1))
+
+
 def select(rewards, hist, u_prompt, u_comp, r_q: float, r_o: float,
-           ddof: int = 1, eps: float = 1e-6, bottom_frac: float = 0.5) -> dict:
+           ddof: int = 1, eps: float = 1e-6, bottom_frac: float = 0.5,
+           fixed_count: bool = False, realised_rate: bool = True) -> dict:
     """Advantages, prune masks and importance-rescaling weights for one batch.
 
     Pruning is the Bernoulli form of Eq. 15 / Eq. 17 with caller-supplied uniforms:
@@ -98,6 +110,14 @@ def select(rewards, hist, u_prompt, u_comp, r_q: float, r_o: float,
     skips prompt-level pruning (first epoch), u_*=None skips that level.
     A pruned prompt drops all its completions. Advantages always come from the
     full group (Alg. 1 computes them before pruning).
+
+    fixed_count=True is the form of App. A / Alg. 1: exactly floor(r * |candidates|) of each
+    candidate set are pruned. Reading: the paper does not say which ones; here they are the
+    candidates with the smallest uniforms (ties to the lower index), i.e. a uniformly random
+    subset of fixed size, so every candidate is pruned with probability m/n. With
+    realised_rate=True that realised rate m/n replaces r in Eq. 18, which keeps the estimator
+    exactly unbiased; realised_rate=False uses the nominal r as Eq. 18 is printed (unbiased
+    only when r * n is an integer).
 
     Weights follow Eq. 18 with the realised counts:
         gamma_q[k]   = (|S^q| / Q) / (1 - P^q[k])
@@ -118,21 +138,42 @@ def select(rewards, hist, u_prompt, u_comp, r_q: float, r_o: float,
         inB_eff = np.zeros(Q, dtype=bool)
     else:
         inB_eff = inB
-    Pq = np.where(inB_eff, rq, 0.0)
-    Po = np.where(cand, ro, 0.0) if u_comp is not None else np.zeros((Q, G))
-
-    keep_prompt = np.ones(Q, dtype=np.uint8)
-    if u_prompt is not None:
-        up = np.asarray(u_prompt, dtype=np.float32)
-        for k in range(Q):
-            if inB_eff[k] and up[k] < np.float32(r_q):
-                keep_prompt[k] = 0
-    keep_comp = np.zeros((Q, G), dtype=np.uint8)
     uc = None if u_comp is None else np.asarray(u_comp, dtype=np.float32).reshape(Q, G)
-    for k in range(Q):
-        for i in range(G):
-            pruned = (uc is not None) and bool(cand[k, i]) and (uc[k, i] < np.float32(r_o))
-            keep_comp[k, i] = 1 if (keep_prompt[k] and not pruned) else 0
+    keep_prompt = np.ones(Q, dtype=np.uint8)
+    keep_comp = np.zeros((Q, G), dtype=np.uint8)
+    Pq = np.zeros(Q)
+    Po = np.zeros((Q, G))
+    if not fixed_count:
+        Pq = np.where(inB_eff, rq, 0.0)
+        Po = np.where(cand, ro, 0.0) if uc is not None else np.zeros((Q, G))
+        if u_prompt is not None:
+            up = np.asarray(u_prompt, dtype=np.float32)
+            for k in range(Q):
+                if inB_eff[k] and up[k] < np.float32(r_q):
+                    keep_prompt[k] = 0
+        for k in range(Q):
+            for i in range(G):
+                pruned = (uc is not None) and bool(cand[k, i]) and (uc[k, i] < np.float32(r_o))
+                keep_comp[k, i] = 1 if (keep_prompt[k] and not pruned) else 0
+    else:
+        if u_prompt is not None:
+            up = np.asarray(u_prompt, dtype=np.float32)
+            B = [k for k in range(Q) if inB_eff[k]]
+            m_q = fixed_prune_count(r_q, len(B))
+            for k in sorted(B, key=lambda k: (float(up[k]), k))[:m_q]:
+                keep_prompt[k] = 0
+            for k in B:
+                Pq[k] = (m_q / len(B)) if realised_rate else rq
+        for k in range(Q):
+            pruned_set = set()
+            if uc is not None:
+                Ck = [i for i in range(G) if cand[k, i]]
+                m_o = fixed_prune_count(r_o, len(Ck))
+                pruned_set = set(sorted(Ck, key=lambda i: (float(uc[k, i]), i))[:m_o])
+                for i in Ck:
+                    Po[k, i] = (m_o / len(Ck)) if realised_rate else ro
+            for i in range(G):
+                keep_comp[k, i] = 1 if (keep_prompt[k] and i not in pruned_set) else 0
 
     n_q = int(keep_prompt.sum())
     n_o = keep_comp.sum(axis=1).astype(np.int64)
@@ -152,6 +193,18 @@ def select(rewards, hist, u_prompt, u_comp, r_q: float, r_o: float,
                 gamma_q=gamma_q, gamma_o=gamma_o, coef=coef,
                 counts=np.concatenate([[n_q], n_o]).astype(np.int32),
                 P_q=Pq, P_o=Po)
+
+
+def history_update(hist_table, prompt_index, keep_prompt, mean_abs_adv) -> np.ndarray:
+    """Carry-forward history score of Eq. 16: a prompt selected in this epoch gets its fresh
+    mean |A|; a prompt that was pruned (no rollout, no new statistics) keeps its last score.
+    hist_table is the score of every prompt of the dataset, prompt_index the dataset index of
+    each prompt of the batch. Returns the updated table (float32)."""
+    out = np.array(hist_table, dtype=np.float32, copy=True)
+    for b, q in enumerate(np.asarray(prompt_index, dtype=np.int64)):
+        if keep_prompt[b]:
+            out[q] = np.float32(mean_abs_adv[b])
+    return out
 
 
 # ----------------------------------------------------------------------------

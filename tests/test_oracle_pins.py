@@ -191,6 +191,90 @@ def test_weights_equal_horvitz_thompson_form():
     assert np.array_equal(s["counts"][1:], kept.sum(axis=1))
 
 
+# ------------------------------------------------- fixed-count pruning, history
+def test_fixed_prune_count_floor_with_float32_rates():
+    assert O.fixed_prune_count(0.9, 10) == 9          # float32(0.9) * 10 is just below 9
+    assert O.fixed_prune_count(0.5, 3) == 1 and O.fixed_prune_count(0.5, 1) == 0
+    assert O.fixed_prune_count(0.7, 100) == 70 and O.fixed_prune_count(0.0, 5) == 0
+    assert O.fixed_prune_count(0.999999, 4) == 3      # someone always survives
+    assert O.fixed_prune_count(0.5, 0) == 0
+
+
+def _enumerate_fixed_subsets(rewards, hist, r_q, r_o):
+    """Every equally likely outcome of fixed-count pruning, realised through the uniforms."""
+    Q, G = rewards.shape
+    inB = O.prompt_candidates(hist, 0.5)
+    cand = O.completion_candidates(rewards)
+    B = [k for k in range(Q) if inB[k]]
+    m_q = O.fixed_prune_count(r_q, len(B))
+    groups = [[i for i in range(G) if cand[k, i]] for k in range(Q)]
+    m_o = [O.fixed_prune_count(r_o, len(g)) for g in groups]
+    choices = [list(itertools.combinations(B, m_q))] + \
+              [list(itertools.combinations(groups[k], m_o[k])) for k in range(Q)]
+    n_total = 1
+    for c in choices:
+        n_total *= len(c)
+    for combo in itertools.product(*choices):
+        up = np.full(Q, 0.9, dtype=np.float32)
+        uc = np.full((Q, G), 0.9, dtype=np.float32)
+        for k in combo[0]:
+            up[k] = 0.1
+        for k in range(Q):
+            for i in combo[1 + k]:
+                uc[k, i] = 0.1
+        yield 1.0 / n_total, up, uc, (m_q, m_o)
+
+
+@pytest.mark.parametrize("Q,G,r_q,r_o,seed", [(4, 3, 0.5, 0.5, 0), (4, 4, 0.75, 0.4, 1), (2, 5, 0.5, 0.7, 2)])
+def test_fixed_count_pruning_counts_and_unbiased_weights(Q, G, r_q, r_o, seed):
+    rng = np.random.default_rng(seed)
+    rewards = (rng.random((Q, G)) < 0.5).astype(np.float32)
+    hist = rng.random(Q).astype(np.float32)
+    acc = np.zeros((Q, G))
+    acc_nominal = np.zeros((Q, G))
+    for prob, up, uc, (m_q, m_o) in _enumerate_fixed_subsets(rewards, hist, r_q, r_o):
+        s = O.select(rewards, hist, up, uc, r_q, r_o, fixed_count=True)
+        assert Q - s["keep_prompt"].sum() == m_q                    # exactly floor(r |B|) prompts go
+        for k in range(Q):
+            if s["keep_prompt"][k]:
+                assert G - s["keep_comp"][k].sum() == m_o[k]        # and floor(r |C_k|) completions
+            else:
+                assert s["keep_comp"][k].sum() == 0
+        acc += prob * s["coef"]
+        acc_nominal += prob * O.select(rewards, hist, up, uc, r_q, r_o, fixed_count=True, realised_rate=False)["coef"]
+    # with the realised rate in Eq. 18 the expected weight is the plain GRPO weight, exactly
+    assert np.allclose(acc, 1.0 / (Q * G), rtol=1e-12)
+    # with the nominal rate it is so only where r * n is an integer
+    inB = O.prompt_candidates(hist, 0.5)
+    cand = O.completion_candidates(rewards)
+    nB = int(inB.sum())
+    for k in range(Q):
+        nC = int(cand[k].sum())
+        exact_q = (not inB[k]) or abs(r_q * nB - round(r_q * nB)) < 1e-9
+        for i in range(G):
+            exact_o = (not cand[k, i]) or abs(r_o * nC - round(r_o * nC)) < 1e-6
+            if exact_q and exact_o:
+                assert math.isclose(acc_nominal[k, i], 1.0 / (Q * G), rel_tol=1e-6)
+
+
+def test_fixed_count_picks_smallest_uniforms_ties_to_lower_index():
+    rewards = np.array([[1, 0, 0, 0, 0, 0]], dtype=np.float32)      # five zeros are the candidates
+    uc = np.array([[0.0, 0.5, 0.2, 0.2, 0.9, 0.1]], dtype=np.float32)
+    s = O.select(rewards, None, None, uc, 0.0, 0.6, fixed_count=True)   # floor(0.6 * 5) = 3 pruned
+    assert s["keep_comp"].tolist() == [[1, 1, 0, 0, 1, 0]]          # 0.1, then the tie 0.2/0.2: both go
+    s = O.select(rewards, None, None, uc, 0.0, 0.4, fixed_count=True)   # 2 pruned: 0.1 and the first 0.2
+    assert s["keep_comp"].tolist() == [[1, 1, 0, 1, 1, 0]]
+    assert math.isclose(s["gamma_o"][0, 1], (4 / 6) / (1 - 2 / 5), rel_tol=1e-12)
+    assert s["gamma_o"][0, 0] == 4 / 6                               # never a candidate: P = 0
+
+
+def test_history_update_carries_pruned_prompts_forward():
+    table = np.array([0.0, 0.3, 0.0, 0.8, 0.5], dtype=np.float32)
+    out = O.history_update(table, [3, 0, 4], [1, 0, 1], [0.25, 0.9, 0.0])
+    assert out.tolist() == [0.0, np.float32(0.3), 0.0, 0.25, 0.0]   # prompt 0 was pruned: unchanged
+    assert table[3] == np.float32(0.8)                              # input untouched
+
+
 # -------------------------------------------------------------------- packing
 def _next_fit(lens, cap):
     rows, cur, rem = [], [], cap
