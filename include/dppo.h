@@ -54,7 +54,9 @@ const char* dppo_last_error(void);
  *                   the lower index; none if hist or u_prompt is NULL (first epoch)(Eq. 17)
  *   masks: a candidate prompt is pruned iff u_prompt[k] < r_q, a candidate completion iff
  *                   u_comp[k,i] < r_o (float32 compares); completions of a pruned prompt
- *                   are dropped; u_comp NULL = no completion pruning
+ *                   are dropped; u_comp NULL = no completion pruning. With fixed_count the
+ *                   floor(r n) candidates with the smallest uniforms are pruned instead
+ *                   (App. A, Alg. 1; floor taken after scaling r n by 1 + 1e-6 because r is float32)
  *   gamma_q[k]   = (|S^q|/Q) / (1 - P^q_k),  gamma_o[k,i] = (|S^o_k|/G) / (1 - P^o_{k,i})
  *                   with the realised retained counts; 0 for pruned entries      (Eq. 18)
  *   coef[k,i]    = gamma_q gamma_o / (|S^q| |S^o_k|): weight of sequence (k,i) in the batch
@@ -72,6 +74,11 @@ typedef struct {
     float adv_eps;      /* added to the standard deviation (1e-6 customary)       */
     int32_t std_ddof;   /* 0 = population, 1 = sample standard deviation          */
     float bottom_frac;  /* fraction of prompts that are candidates (paper: 0.5)   */
+    int32_t fixed_count;    /* 0: Bernoulli pruning (u < r); 1: exactly floor(r n) of each
+                               candidate set of n are pruned (App. A, Alg. 1): those with the
+                               smallest (uniform, index); one candidate always survives      */
+    int32_t realised_rate;  /* fixed_count only. 1: Eq. 18 uses the realised rate floor(r n)/n
+                               (exactly unbiased); 0: the nominal r, as the equation is printed */
 } dppo_select_params;
 
 int dppo_select(const dppo_select_params* p,
@@ -81,6 +88,15 @@ int dppo_select(const dppo_select_params* p,
                 uint8_t* keep_prompt, uint8_t* keep_comp,
                 float* gamma_q, float* gamma_o, float* coef,
                 int32_t* counts, void* stream);
+
+/* dppo_history_update -- Sec. 4.2 Eq. 16 (carry-forward history score).
+ * For the n prompts of a batch, prompt b being entry prompt_index[b] of the dataset-wide
+ * score table hist_table[table_size]: a prompt retained in this epoch (keep_prompt[b] != 0)
+ * takes its fresh score mean_abs_adv[b]; a pruned prompt keeps its last score. Indices
+ * outside the table are ignored; indices must be distinct within a call.
+ */
+int dppo_history_update(int32_t n, const int32_t* prompt_index, const uint8_t* keep_prompt,
+                        const float* mean_abs_adv, float* hist_table, int64_t table_size, void* stream);
 
 /* --------------------------------------------------------------------------------
  * dppo_pack -- Sec. 4.3 (Dense Prompt Packing), applied to the retained sequences.

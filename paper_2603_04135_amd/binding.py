@@ -19,7 +19,7 @@ _lib = None
 
 EXPORTS = ["dppo_status_str", "dppo_last_error", "dppo_select", "dppo_pack", "dppo_gather_f32",
            "dppo_workspace_bytes", "dppo_workspace_min_bytes", "dppo_token_logprob", "dppo_loss_fwd_bwd",
-           "dppo_timing_enable", "dppo_timing_read"]
+           "dppo_timing_enable", "dppo_timing_read", "dppo_history_update"]
 STAGES = ["logits_gemm", "grad_logits", "dh_gemm", "dw_gemm"]
 
 
@@ -31,7 +31,8 @@ class DppoError(RuntimeError):
 
 class SelectParams(ctypes.Structure):
     _fields_ = [("Q", c_int32), ("G", c_int32), ("r_q", c_float), ("r_o", c_float),
-                ("adv_eps", c_float), ("std_ddof", c_int32), ("bottom_frac", c_float)]
+                ("adv_eps", c_float), ("std_ddof", c_int32), ("bottom_frac", c_float),
+                ("fixed_count", c_int32), ("realised_rate", c_int32)]
 
 
 class PackParams(ctypes.Structure):
@@ -79,6 +80,8 @@ def load():
     lib.dppo_loss_fwd_bwd.restype = c_int
     lib.dppo_loss_fwd_bwd.argtypes = ([POINTER(HeadShape), POINTER(LossParams), c_int32] + [c_void_p] * 16
                                       + [c_size_t, c_void_p])
+    lib.dppo_history_update.restype = c_int
+    lib.dppo_history_update.argtypes = [c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_void_p]
     lib.dppo_timing_enable.restype = c_int
     lib.dppo_timing_enable.argtypes = [c_int]
     lib.dppo_timing_read.restype = c_int
@@ -126,7 +129,8 @@ def _dtype_code(t: torch.Tensor) -> int:
 
 # --------------------------------------------------------------------------------------
 def dppo_select(rewards, hist, u_prompt, u_comp, r_q: float, r_o: float, adv_eps: float = 1e-6,
-                std_ddof: int = 1, bottom_frac: float = 0.5, device="cuda:0") -> dict:
+                std_ddof: int = 1, bottom_frac: float = 0.5, fixed_count: bool = False,
+                realised_rate: bool = True, device="cuda:0") -> dict:
     """rewards [Q,G]; hist/u_prompt [Q] or None; u_comp [Q,G] or None. Returns device tensors."""
     lib = load()
     rewards = _as(rewards, torch.float32, device)
@@ -140,13 +144,29 @@ def dppo_select(rewards, hist, u_prompt, u_comp, r_q: float, r_o: float, adv_eps
                keep_comp=torch.empty((Q, G), dtype=torch.uint8, device=device),
                gamma_q=torch.empty(Q, **f32), gamma_o=torch.empty((Q, G), **f32),
                coef=torch.empty((Q, G), **f32), counts=torch.empty(1 + Q, dtype=torch.int32, device=device))
-    p = SelectParams(Q, G, r_q, r_o, adv_eps, std_ddof, bottom_frac)
+    p = SelectParams(Q, G, r_q, r_o, adv_eps, std_ddof, bottom_frac, 1 if fixed_count else 0,
+                     1 if realised_rate else 0)
     st = lib.dppo_select(ctypes.byref(p), _ptr(rewards), _ptr(hist), _ptr(u_prompt), _ptr(u_comp),
                          _ptr(out["adv"]), _ptr(out["mean_abs_adv"]), _ptr(out["keep_prompt"]),
                          _ptr(out["keep_comp"]), _ptr(out["gamma_q"]), _ptr(out["gamma_o"]), _ptr(out["coef"]),
                          _ptr(out["counts"]), _stream(device))
     _check(st, "dppo_select")
     return out
+
+
+def dppo_history_update(hist_table: torch.Tensor, prompt_index, keep_prompt, mean_abs_adv) -> torch.Tensor:
+    """Updates hist_table (float32 device tensor) in place and returns it."""
+    lib = load()
+    device = hist_table.device
+    if hist_table.dtype != torch.float32:
+        raise ValueError("hist_table must be float32")
+    prompt_index = _as(prompt_index, torch.int32, device)
+    keep_prompt = _as(keep_prompt, torch.uint8, device)
+    mean_abs_adv = _as(mean_abs_adv, torch.float32, device)
+    st = lib.dppo_history_update(prompt_index.numel(), _ptr(prompt_index), _ptr(keep_prompt), _ptr(mean_abs_adv),
+                                 _ptr(hist_table), hist_table.numel(), _stream(device))
+    _check(st, "dppo_history_update")
+    return hist_table
 
 
 def dppo_pack(prompt_len, comp_len, keep, capacity: int, n_win: int, loss_pos_capacity: Optional[int] = None,

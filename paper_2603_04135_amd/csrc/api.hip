@@ -217,10 +217,22 @@ int dppo_select(const dppo_select_params* p, const float* rewards, const float* 
         return fail(DPPO_ERR_INVALID_ARG, "prune probabilities must lie in [0,1) (r_q=%g r_o=%g)", p->r_q, p->r_o);
     if (!(p->adv_eps >= 0.0f)) return fail(DPPO_ERR_INVALID_ARG, "adv_eps must be >= 0");
     if (!(p->bottom_frac >= 0.0f && p->bottom_frac <= 1.0f)) return fail(DPPO_ERR_INVALID_ARG, "bottom_frac must lie in [0,1]");
+    if ((p->fixed_count != 0 && p->fixed_count != 1) || (p->realised_rate != 0 && p->realised_rate != 1))
+        return fail(DPPO_ERR_INVALID_ARG, "fixed_count and realised_rate must be 0 or 1");
     const int n_bottom = (int)std::floor((double)p->bottom_frac * (double)p->Q);
     launch_select(*p, n_bottom, rewards, hist, u_prompt, u_comp, adv, mean_abs_adv, keep_prompt, keep_comp, gamma_q,
                   gamma_o, coef, counts, (hipStream_t)stream);
     return check_launch("dppo_select");
+}
+
+int dppo_history_update(int32_t n, const int32_t* prompt_index, const uint8_t* keep_prompt,
+                        const float* mean_abs_adv, float* hist_table, int64_t table_size, void* stream) {
+    if (n < 0 || table_size < 0) return fail(DPPO_ERR_SHAPE, "n and table_size must be >= 0");
+    if (n == 0) return DPPO_OK;
+    if (!prompt_index || !keep_prompt || !mean_abs_adv || !hist_table)
+        return fail(DPPO_ERR_INVALID_ARG, "a required array pointer is NULL");
+    launch_history_update(n, prompt_index, keep_prompt, mean_abs_adv, hist_table, table_size, (hipStream_t)stream);
+    return check_launch("dppo_history_update");
 }
 
 int dppo_pack(const dppo_pack_params* p, const int32_t* prompt_len, const int32_t* comp_len, const uint8_t* keep,

@@ -22,6 +22,9 @@ void launch_select(const dppo_select_params& p, int n_bottom, const float* rewar
                    uint8_t* keep_prompt, uint8_t* keep_comp, float* gamma_q, float* gamma_o,
                    float* coef, int32_t* counts, hipStream_t st);
 
+void launch_history_update(int32_t n, const int32_t* prompt_index, const uint8_t* keep_prompt,
+                           const float* mean_abs_adv, float* hist_table, int64_t table_size, hipStream_t st);
+
 // ---- packing (pack.hip) -----------------------------------------------------
 void launch_pack(const dppo_pack_params& p, const int32_t* prompt_len, const int32_t* comp_len,
                  const uint8_t* keep, int32_t* order, int32_t* row_ptr, int32_t* cu, int32_t* lcu,

@@ -19,9 +19,11 @@ def lib():
     return P
 
 
-def _cmp_select(P, rewards, hist, up, uc, r_q, r_o, ddof=1, eps=1e-6, bottom=0.5):
-    ref = O.select(rewards, hist, up, uc, r_q, r_o, ddof=ddof, eps=eps, bottom_frac=bottom)
-    got = P.dppo_select(rewards, hist, up, uc, r_q, r_o, adv_eps=eps, std_ddof=ddof, bottom_frac=bottom, device=DEV)
+def _cmp_select(P, rewards, hist, up, uc, r_q, r_o, ddof=1, eps=1e-6, bottom=0.5, fixed=False, realised=True):
+    ref = O.select(rewards, hist, up, uc, r_q, r_o, ddof=ddof, eps=eps, bottom_frac=bottom, fixed_count=fixed,
+                   realised_rate=realised)
+    got = P.dppo_select(rewards, hist, up, uc, r_q, r_o, adv_eps=eps, std_ddof=ddof, bottom_frac=bottom,
+                        fixed_count=fixed, realised_rate=realised, device=DEV)
     g = {k: v.cpu().numpy() for k, v in got.items()}
     assert np.array_equal(g["keep_prompt"], ref["keep_prompt"])
     assert np.array_equal(g["keep_comp"], ref["keep_comp"])
@@ -63,6 +65,45 @@ def test_select_edge_cases(lib):
     r = (rng.random((6, 4)) < 0.5).astype(np.float32)
     ref, _ = _cmp_select(lib, r, np.zeros(6, np.float32), np.zeros(6, np.float32), np.zeros((6, 4), np.float32), 0.9, 0.9)
     assert ref["keep_prompt"].sum() == 3
+
+
+@pytest.mark.parametrize("name", list(WL.WORKLOADS))
+def test_fixed_count_select_matches_oracle(lib, name):
+    rb = WL.make_rollout(name)
+    wl = rb.wl
+    for realised in (True, False):
+        ref, _ = _cmp_select(lib, rb.rewards, rb.hist, rb.u_prompt, rb.u_comp, wl.r_q, wl.r_o, fixed=True,
+                             realised=realised)
+    n_b = wl.Q // 2
+    assert wl.Q - ref["keep_prompt"].sum() == O.fixed_prune_count(wl.r_q, n_b)
+    _cmp_select(lib, rb.rewards, None, None, rb.u_comp, wl.r_q, wl.r_o, fixed=True)
+    _cmp_select(lib, rb.rewards, rb.hist, rb.u_prompt, None, wl.r_q, wl.r_o, fixed=True)
+    # rates that are not float32-exact, tied uniforms
+    u_tied = np.round(rb.u_comp, 1).astype(np.float32)
+    for r in (0.9, 0.7, 0.3, 0.0):
+        _cmp_select(lib, rb.rewards, rb.hist, np.round(rb.u_prompt, 1).astype(np.float32), u_tied, r, r, fixed=True)
+
+
+def test_history_update_matches_oracle(lib):
+    rng = np.random.default_rng(3)
+    table = rng.random(1000).astype(np.float32)
+    idx = rng.permutation(1000)[:256].astype(np.int32)
+    keep = (rng.random(256) < 0.6).astype(np.uint8)
+    score = rng.random(256).astype(np.float32)
+    ref = O.history_update(table, idx, keep, score)
+    t = torch.as_tensor(table.copy(), device=DEV)
+    got = lib.dppo_history_update(t, idx, keep, score).cpu().numpy()
+    assert np.array_equal(got, ref)
+    assert (got != table).sum() == int(keep.sum())
+    # a select -> update round trip: the emitted mean |A| becomes the next epoch's score
+    rb = WL.make_rollout("small")
+    sel = lib.dppo_select(rb.rewards, rb.hist, rb.u_prompt, rb.u_comp, 0.4, 0.5, fixed_count=True, device=DEV)
+    t = torch.as_tensor(rb.hist.copy(), device=DEV)
+    lib.dppo_history_update(t, np.arange(rb.wl.Q, dtype=np.int32), sel["keep_prompt"], sel["mean_abs_adv"])
+    o = O.select(rb.rewards, rb.hist, rb.u_prompt, rb.u_comp, 0.4, 0.5, fixed_count=True)
+    want = O.history_update(rb.hist, np.arange(rb.wl.Q), o["keep_prompt"], o["mean_abs_adv"].astype(np.float32))
+    assert np.allclose(t.cpu().numpy(), want, rtol=2e-6, atol=1e-9)
+    assert np.array_equal(t.cpu().numpy()[o["keep_prompt"] == 0], rb.hist[o["keep_prompt"] == 0])
 
 
 def test_select_rejects_bad_arguments(lib):

@@ -42,12 +42,12 @@ def test_status_strings(lib):
 def test_host_side_validation_launches_nothing(lib):
     from paper_2603_04135_amd.binding import HeadShape, LossParams, PackParams, SelectParams
     one = ctypes.c_void_p(256)   # never dereferenced: validation fails first
-    sp = SelectParams(4, 4, 1.0, 0.5, 1e-6, 1, 0.5)       # r_q outside [0,1)
+    sp = SelectParams(4, 4, 1.0, 0.5, 1e-6, 1, 0.5, 0, 1)       # r_q outside [0,1)
     assert lib.dppo_select(ctypes.byref(sp), *([one] * 12), None) == 1
     assert b"[0,1)" in lib.dppo_last_error()
-    sp = SelectParams(4, 1, 0.5, 0.5, 1e-6, 1, 0.5)       # sample std of one completion
+    sp = SelectParams(4, 1, 0.5, 0.5, 1e-6, 1, 0.5, 0, 1)       # sample std of one completion
     assert lib.dppo_select(ctypes.byref(sp), *([one] * 12), None) == 2
-    sp = SelectParams(4, 4, 0.5, 0.5, 1e-6, 1, 0.5)
+    sp = SelectParams(4, 4, 0.5, 0.5, 1e-6, 1, 0.5, 0, 1)
     assert lib.dppo_select(ctypes.byref(sp), None, *([one] * 11), None) == 1
     pp = PackParams(0, 16, 4)
     assert lib.dppo_pack(ctypes.byref(pp), *([one] * 8), 10, one, None) == 2
