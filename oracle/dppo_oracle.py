@@ -210,31 +210,42 @@ def history_update(hist_table, prompt_index, keep_prompt, mean_abs_adv) -> np.nd
 # ----------------------------------------------------------------------------
 # Sec. 4.3: Dense Prompt Packing (window-based greedy selection)
 # ----------------------------------------------------------------------------
-def pack(prompt_len, comp_len, keep, capacity: int, n_win: int) -> dict:
-    """Window-based greedy packing of the kept sequences into rows of `capacity` tokens.
+def pack(prompt_len, comp_len, keep, capacity, n_win: int, policy: str = "first_fit") -> dict:
+    """Window-based greedy packing of the kept sequences into rows of `capacity` tokens (Sec. 4.3).
 
     Items are the kept sequences in index order, length = prompt + completion.
     A pool holds up to n_win items in arrival order and is refilled from the stream
-    after every placement. For each row, the pool is scanned from its oldest item
-    to its newest (items fetched during the scan included) and every item that
-    still fits the remaining space is placed (reading: first-fit in arrival order;
-    the paper only says "greedily select samples that fit").
+    after every placement. The paper only says that samples of the pool that fit the
+    remaining space are selected greedily; two readings are offered:
+      "first_fit": the pool is scanned from its oldest item to its newest (items fetched
+                   during the scan included) and every item that still fits is placed;
+      "best_fit":  the longest pool item that fits is placed (oldest among equals), and
+                   this repeats, refilled items included, until no pool item fits.
+
+    comp_len=None packs prompts alone, the paper's own use at dataset initialisation:
+    no loss positions exist then. capacity=None or 0 takes L_max = the longest kept item.
 
     Returns order (original item indices in packed order), row_ptr (row boundaries
     in sequences), cu_seqlens (token offsets of the packed sequences), loss_cu
-    (offsets into the compact loss-token index) and loss_pos (packed positions
+    (offsets into the compact loss-token index), loss_pos (packed positions
     whose hidden state predicts a completion token: for a sequence starting at c
-    with prompt P and completion C these are c+P-1 ... c+P+C-2).
+    with prompt P and completion C these are c+P-1 ... c+P+C-2), the capacity used and
+    density = T / (n_rows * capacity), the share of row slots that hold a real token.
     """
     pl = np.asarray(prompt_len, dtype=np.int64)
-    cl = np.asarray(comp_len, dtype=np.int64)
+    prompts_only = comp_len is None
+    cl = np.zeros_like(pl) if prompts_only else np.asarray(comp_len, dtype=np.int64)
     n_all = pl.shape[0]
     kept = [j for j in range(n_all) if keep is None or keep[j]]
+    if not capacity:
+        capacity = max([int(pl[j] + cl[j]) for j in kept], default=1)
     for j in kept:
-        if pl[j] < 1 or cl[j] < 1 or pl[j] + cl[j] > capacity:
+        if pl[j] < 1 or (cl[j] < 1 and not prompts_only) or pl[j] + cl[j] > capacity:
             raise ValueError("item %d does not fit a row or has an empty part" % j)
     if n_win < 1:
         raise ValueError("n_win must be >= 1")
+    if policy not in ("first_fit", "best_fit"):
+        raise ValueError("unknown policy %r" % (policy,))
     n = len(kept)
     stream = list(kept)
     pool = stream[:min(n_win, n)]
@@ -242,19 +253,35 @@ def pack(prompt_len, comp_len, keep, capacity: int, n_win: int) -> dict:
     order, row_ptr = [], [0]
     while pool:
         rem = capacity
-        pos = 0
-        while pos < len(pool):
-            j = pool[pos]
-            ell = int(pl[j] + cl[j])
-            if ell <= rem:
+        if policy == "first_fit":
+            pos = 0
+            while pos < len(pool):
+                j = pool[pos]
+                ell = int(pl[j] + cl[j])
+                if ell <= rem:
+                    order.append(j)
+                    rem -= ell
+                    del pool[pos]
+                    if nxt < n:
+                        pool.append(stream[nxt])
+                        nxt += 1
+                else:
+                    pos += 1
+        else:
+            while True:
+                best = -1
+                for pos, j in enumerate(pool):
+                    ell = int(pl[j] + cl[j])
+                    if ell <= rem and (best < 0 or ell > int(pl[pool[best]] + cl[pool[best]])):
+                        best = pos
+                if best < 0:
+                    break
+                j = pool.pop(best)
                 order.append(j)
-                rem -= ell
-                del pool[pos]
+                rem -= int(pl[j] + cl[j])
                 if nxt < n:
                     pool.append(stream[nxt])
                     nxt += 1
-            else:
-                pos += 1
         row_ptr.append(len(order))
     cu = [0]
     lcu = [0]
@@ -268,7 +295,8 @@ def pack(prompt_len, comp_len, keep, capacity: int, n_win: int) -> dict:
     return dict(order=np.array(order, dtype=np.int32), row_ptr=np.array(row_ptr, dtype=np.int32),
                 cu_seqlens=np.array(cu, dtype=np.int32), loss_cu=np.array(lcu, dtype=np.int32),
                 loss_pos=np.array(loss_pos, dtype=np.int32),
-                n_rows=len(row_ptr) - 1, T=cu[-1], N=lcu[-1], S=n)
+                n_rows=len(row_ptr) - 1, T=cu[-1], N=lcu[-1], S=n, capacity=int(capacity),
+                density=(cu[-1] / ((len(row_ptr) - 1) * capacity)) if n else 0.0)
 
 
 # ----------------------------------------------------------------------------

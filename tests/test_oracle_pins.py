@@ -387,6 +387,89 @@ def test_pack_equal_lengths_and_keep_mask():
         O.pack(np.array([6]), np.array([6]), None, 10, 2)
 
 
+def _window_best_fit(lens, cap, n_win):
+    """Best-fit reading without an explicit pool: after p placements the pool is the set of unplaced
+    items among the first n_win + p of the stream; take the longest that fits, oldest among equals."""
+    n = len(lens)
+    placed = [False] * n
+    n_placed, rows = 0, []
+    while n_placed < n:
+        row, rem = [], cap
+        while True:
+            visible = [j for j in range(min(n, n_win + n_placed)) if not placed[j] and lens[j] <= rem]
+            if not visible:
+                break
+            j = sorted(visible, key=lambda t: (-lens[t], t))[0]
+            placed[j] = True
+            n_placed += 1
+            row.append(j)
+            rem -= lens[j]
+        rows.append(row)
+    return rows
+
+
+def test_pack_best_fit_policy():
+    ones = np.ones(5, dtype=np.int64)
+    # pool {4,6,3}: take 6, refill 5, take 4 (row full); then 5, 3, 2
+    p = O.pack(ones, np.array([4, 6, 3, 5, 2]) - 1, None, 10, 3, policy="best_fit")
+    assert p["order"].tolist() == [1, 0, 3, 2, 4] and p["row_ptr"].tolist() == [0, 2, 5]
+    # a case where the two readings differ in the number of rows
+    lens = np.array([5, 4, 6, 5])
+    ff = O.pack(ones[:4], lens - 1, None, 10, 4)
+    bf = O.pack(ones[:4], lens - 1, None, 10, 4, policy="best_fit")
+    assert _rows_of(ff) == [[0, 1], [2], [3]] and _rows_of(bf) == [[2, 1], [0, 3]]
+    assert ff["density"] == pytest.approx(20 / 30) and bf["density"] == 1.0
+    rng = np.random.default_rng(23)
+    for trial in range(200):
+        n = int(rng.integers(1, 40))
+        cap = int(rng.integers(8, 64))
+        pl = rng.integers(1, cap // 2 + 1, size=n)
+        cl = rng.integers(1, cap - pl + 1)
+        lens = (pl + cl).tolist()
+        for n_win in (1, 2, 5, n, n + 7):
+            p = O.pack(pl, cl, None, cap, n_win, policy="best_fit")
+            rows = _rows_of(p)
+            assert sorted(p["order"].tolist()) == list(range(n))
+            assert all(sum(lens[j] for j in row) <= cap for row in rows)
+            assert rows == _window_best_fit(lens, cap, n_win)
+            if n_win == 1:
+                assert rows == _next_fit(lens, cap)
+            if n_win >= n:
+                # every row opens with the longest item still unplaced
+                left = set(range(n))
+                for row in rows:
+                    assert lens[row[0]] == max(lens[j] for j in left)
+                    left -= set(row)
+            assert p["density"] == pytest.approx(sum(lens) / (p["n_rows"] * cap))
+    with pytest.raises(ValueError):
+        O.pack(ones, ones, None, 10, 2, policy="worst_fit")
+
+
+def test_pack_prompts_alone_with_longest_item_as_capacity():
+    # Sec. 4.3: prompts are packed before any rollout, L_max = the longest sample
+    pl = np.array([3, 9, 4, 2, 5, 9, 1])
+    for policy in ("first_fit", "best_fit"):
+        p = O.pack(pl, None, None, None, 3, policy=policy)
+        assert p["capacity"] == 9 and p["N"] == 0 and len(p["loss_pos"]) == 0
+        assert p["loss_cu"].tolist() == [0] * 8
+        assert p["T"] == 33 and sorted(p["order"].tolist()) == list(range(7))
+        assert np.array_equal(np.diff(p["cu_seqlens"]), pl[p["order"]])
+    # first fit, window 3, worked by hand (items fetched during a scan are still visited by it):
+    p = O.pack(pl, None, None, None, 3)
+    #   row 0: pool (3,9,4): 3 -> fetch 2: pool (9,4,2): 9 no, 4 (rem 2) -> fetch 5: 2 (rem 0) -> fetch 9
+    #   row 1: pool (9,5,9): 9 (rem 0) -> fetch 1
+    #   row 2: pool (5,9,1): 5 (rem 4), 9 no, 1 (rem 3)
+    #   row 3: pool (9): 9
+    assert _rows_of(p) == [[0, 2, 3], [1], [4, 6], [5]]
+    assert p["density"] == pytest.approx(33 / 36)
+    # completions may not be empty when they are given
+    with pytest.raises(ValueError):
+        O.pack(pl, np.zeros(7, dtype=np.int64), None, 16, 3)
+    # keep mask decides which items define L_max
+    p = O.pack(pl, None, np.array([1, 0, 1, 1, 1, 0, 1], dtype=np.uint8), 0, 2)
+    assert p["capacity"] == 5 and p["S"] == 5
+
+
 # ------------------------------------------------------------------ log-probs
 def _tiny_head(seed, N=11, D=8, V=16):
     rng = np.random.default_rng(seed)
