@@ -104,8 +104,15 @@ int dppo_history_update(int32_t n, const int32_t* prompt_index, const uint8_t* k
  * Items are the n_items sequences in index order, item j having prompt_len[j] +
  * comp_len[j] tokens; items with keep[j] == 0 are skipped (keep NULL = all kept).
  * A pool of up to n_win items in arrival order is refilled from the stream after every
- * placement; for each row of `capacity` tokens the pool is scanned from oldest to newest
- * (items fetched meanwhile included) and every item that still fits is placed.
+ * placement. The paper leaves the greedy choice inside the pool open; `policy` picks a reading:
+ *   DPPO_PACK_FIRST_FIT  for each row of `capacity` tokens the pool is scanned from oldest to
+ *                        newest (items fetched meanwhile included) and every item that still
+ *                        fits is placed;
+ *   DPPO_PACK_BEST_FIT   the longest pool item that fits is placed (the oldest among equals),
+ *                        repeatedly, refilled items included, until no pool item fits.
+ * comp_len NULL packs prompts alone, the paper's own use before any rollout: loss_cu is then
+ * all zero, N = 0, and loss_pos is not touched (it may be NULL). capacity 0 stands for
+ * L_max = the longest kept item, the paper's definition.
  *
  * Outputs (all int32):
  *   order[s]       original index of the s-th packed sequence           [n_items], S valid
@@ -114,19 +121,23 @@ int dppo_history_update(int32_t n, const int32_t* prompt_index, const uint8_t* k
  *   loss_cu[s]     first loss token of packed sequence s; [S] = N       [n_items+1]
  *   loss_pos[n]    packed position whose hidden state predicts the n-th completion token:
  *                  sequence s contributes cu[s]+P-1 ... cu[s]+P+C-2     [loss_pos_capacity]
- *   meta[8]        {n_rows, T, N, device_status, S, 0, 0, 0}
+ *   meta[8]        {n_rows, T, N, device_status, S, capacity used, 0, 0}; the share of row slots
+ *                  that hold a real token (fill density) is T / (n_rows * capacity used)
  * device_status: 0 ok; 1 = a kept item has prompt_len < 1, comp_len < 1 or does not fit
  * `capacity`; 2 = N exceeds loss_pos_capacity; 3 = T does not fit int32. On a non-zero
  * status n_rows = T = N = S = 0 and no other output is meaningful.
  * cu_seqlens and loss_cu are also used as scratch while packing.
  * The result is a bit-exact function of the inputs (one deterministic wavefront).
  */
+enum { DPPO_PACK_FIRST_FIT = 0, DPPO_PACK_BEST_FIT = 1 };
+
 typedef struct {
     int32_t n_items, capacity, n_win;
+    int32_t policy;   /* DPPO_PACK_FIRST_FIT or DPPO_PACK_BEST_FIT */
 } dppo_pack_params;
 
 int dppo_pack(const dppo_pack_params* p,
-              const int32_t* prompt_len, const int32_t* comp_len, const uint8_t* keep /* or NULL */,
+              const int32_t* prompt_len, const int32_t* comp_len /* or NULL */, const uint8_t* keep /* or NULL */,
               int32_t* order, int32_t* row_ptr, int32_t* cu_seqlens, int32_t* loss_cu,
               int32_t* loss_pos, int64_t loss_pos_capacity, int32_t* meta, void* stream);
 

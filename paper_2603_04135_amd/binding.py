@@ -36,7 +36,10 @@ class SelectParams(ctypes.Structure):
 
 
 class PackParams(ctypes.Structure):
-    _fields_ = [("n_items", c_int32), ("capacity", c_int32), ("n_win", c_int32)]
+    _fields_ = [("n_items", c_int32), ("capacity", c_int32), ("n_win", c_int32), ("policy", c_int32)]
+
+
+PACK_POLICIES = {"first_fit": 0, "best_fit": 1}
 
 
 class HeadShape(ctypes.Structure):
@@ -170,8 +173,9 @@ def dppo_history_update(hist_table: torch.Tensor, prompt_index, keep_prompt, mea
 
 
 def dppo_pack(prompt_len, comp_len, keep, capacity: int, n_win: int, loss_pos_capacity: Optional[int] = None,
-              device="cuda:0") -> dict:
-    """prompt_len, comp_len [n_items] int32; keep [n_items] uint8 or None.
+              device="cuda:0", policy: str = "first_fit") -> dict:
+    """prompt_len, comp_len [n_items] int32 (comp_len None: prompts alone); keep [n_items] uint8 or None;
+    capacity 0 or None: the longest kept item.
 
     Returns device tensors sized for the worst case plus the host copy of meta
     (this is the one place the path synchronises: the caller needs T and N to size H)."""
@@ -181,7 +185,7 @@ def dppo_pack(prompt_len, comp_len, keep, capacity: int, n_win: int, loss_pos_ca
     keep = _as(keep, torch.uint8, device)
     n = prompt_len.numel()
     if loss_pos_capacity is None:
-        loss_pos_capacity = int(comp_len.clamp(min=0).sum().item())
+        loss_pos_capacity = 0 if comp_len is None else int(comp_len.clamp(min=0).sum().item())
     i32 = dict(dtype=torch.int32, device=device)
     order = torch.empty(n, **i32)
     row_ptr = torch.empty(n + 1, **i32)
@@ -189,14 +193,15 @@ def dppo_pack(prompt_len, comp_len, keep, capacity: int, n_win: int, loss_pos_ca
     lcu = torch.empty(n + 1, **i32)
     loss_pos = torch.empty(max(1, loss_pos_capacity), **i32)
     meta = torch.zeros(8, **i32)
-    p = PackParams(n, capacity, n_win)
+    p = PackParams(n, int(capacity or 0), n_win, PACK_POLICIES[policy])
     st = lib.dppo_pack(ctypes.byref(p), _ptr(prompt_len), _ptr(comp_len), _ptr(keep), _ptr(order), _ptr(row_ptr),
                        _ptr(cu), _ptr(lcu), _ptr(loss_pos), loss_pos_capacity, _ptr(meta), _stream(device))
     _check(st, "dppo_pack")
     m = meta.cpu().tolist()
-    n_rows, T, N, dev_status, S = m[0], m[1], m[2], m[3], m[4]
+    n_rows, T, N, dev_status, S, cap = m[0], m[1], m[2], m[3], m[4], m[5]
     return dict(order=order[:S], row_ptr=row_ptr[:n_rows + 1], cu_seqlens=cu[:S + 1], loss_cu=lcu[:S + 1],
-                loss_pos=loss_pos[:N], n_rows=n_rows, T=T, N=N, S=S, device_status=dev_status)
+                loss_pos=loss_pos[:N], n_rows=n_rows, T=T, N=N, S=S, device_status=dev_status, capacity=cap,
+                density=(T / (n_rows * cap)) if n_rows else 0.0)
 
 
 def dppo_gather_f32(idx: torch.Tensor, src: torch.Tensor) -> torch.Tensor:

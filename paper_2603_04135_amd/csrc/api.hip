@@ -239,11 +239,16 @@ int dppo_pack(const dppo_pack_params* p, const int32_t* prompt_len, const int32_
               int32_t* order, int32_t* row_ptr, int32_t* cu_seqlens, int32_t* loss_cu, int32_t* loss_pos,
               int64_t loss_pos_capacity, int32_t* meta, void* stream) {
     if (!p) return fail(DPPO_ERR_INVALID_ARG, "params is NULL");
-    if (!prompt_len || !comp_len || !order || !row_ptr || !cu_seqlens || !loss_cu || !loss_pos || !meta)
+    if (!prompt_len || !order || !row_ptr || !cu_seqlens || !loss_cu || !meta)
         return fail(DPPO_ERR_INVALID_ARG, "a required array pointer is NULL");
+    if (comp_len && !loss_pos) return fail(DPPO_ERR_INVALID_ARG, "loss_pos is NULL although completions are packed");
     if (p->n_items <= 0) return fail(DPPO_ERR_SHAPE, "n_items must be positive (%d)", p->n_items);
-    if (p->capacity < 2) return fail(DPPO_ERR_CAPACITY, "capacity must hold at least a 1+1 token sequence (%d)", p->capacity);
+    if (p->capacity < 0 || (p->capacity != 0 && p->capacity < (comp_len ? 2 : 1)))
+        return fail(DPPO_ERR_CAPACITY, "capacity must be 0 (longest item) or hold the shortest possible item (%d)",
+                    p->capacity);
     if (p->n_win < 1) return fail(DPPO_ERR_INVALID_ARG, "n_win must be at least 1 (%d)", p->n_win);
+    if (p->policy != DPPO_PACK_FIRST_FIT && p->policy != DPPO_PACK_BEST_FIT)
+        return fail(DPPO_ERR_INVALID_ARG, "unknown packing policy %d", p->policy);
     if (loss_pos_capacity < 0) return fail(DPPO_ERR_SHAPE, "loss_pos_capacity is negative");
     launch_pack(*p, prompt_len, comp_len, keep, order, row_ptr, cu_seqlens, loss_cu, loss_pos, loss_pos_capacity,
                 meta, (hipStream_t)stream);

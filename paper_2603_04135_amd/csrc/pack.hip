@@ -2,7 +2,8 @@
 // rows of `capacity` tokens. The algorithm is sequential by definition (each placement
 // changes the remaining space and refills the pool), so it runs in ONE wavefront: the pool
 // is the set of not-yet-placed items among the first `next` stream items, 64 of them are
-// examined per step (one per lane), a ballot finds the oldest item that fits, and the
+// examined per step (one per lane), a ballot finds the oldest item that fits (first-fit
+// reading) or a wave-wide max finds the longest one (best-fit reading), and the
 // wave-uniform state (remaining space, pool end, output position) lives in scalars.
 // Integer work only; the result is a bit-exact function of the inputs.
 #include "dppo_internal.h"
@@ -17,8 +18,16 @@ __device__ __forceinline__ int64_t wave_sum64(int64_t v) {
     return v;
 }
 
+__device__ __forceinline__ int64_t wave_max64(int64_t v) {
+    for (int off = 32; off > 0; off >>= 1) {
+        int64_t o = __shfl_xor(v, off, WAVE);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
 __global__ __launch_bounds__(WAVE) void pack_kernel(
-    int n_items, int capacity, int n_win, const int32_t* __restrict__ prompt_len,
+    int n_items, int capacity, int n_win, int policy, const int32_t* __restrict__ prompt_len,
     const int32_t* __restrict__ comp_len, const uint8_t* __restrict__ keep, int32_t* order,
     int32_t* row_ptr, int32_t* cu /* scratch: stream item length, -1 once placed */,
     int32_t* lcu /* scratch: stream item -> original index */, int64_t loss_pos_capacity, int32_t* meta) {
@@ -28,32 +37,36 @@ __global__ __launch_bounds__(WAVE) void pack_kernel(
     // ---- compact the kept items into the stream, validate, total T and N -------------
     int S = 0;
     int bad = 0;
-    int64_t T = 0, N = 0;
+    int64_t T = 0, N = 0, longest = 1;
+    const int min_c = comp_len != nullptr ? 1 : 0;   // prompts alone: no completion part
     for (int j0 = 0; j0 < n_items; j0 += WAVE) {
         int j = j0 + lane;
         bool kept = j < n_items && (keep == nullptr || keep[j] != 0);
         int P = kept ? prompt_len[j] : 1;
-        int C = kept ? comp_len[j] : 1;
+        int C = (kept && comp_len != nullptr) ? comp_len[j] : min_c;
         int64_t len = (int64_t)P + (int64_t)C;
-        if (kept && (P < 1 || C < 1 || len > (int64_t)capacity)) bad = 1;
+        if (kept && (P < 1 || C < min_c || len > 0x7fffffffLL)) bad = 1;
+        if (kept && len > longest) longest = len;
         uint64_t m = __ballot(kept);
         if (kept) {
             int pos = S + __popcll(m & lanes_below);
-            cu[pos] = (int32_t)(len > (int64_t)capacity ? capacity : len);
+            cu[pos] = (int32_t)(len > 0x7fffffffLL ? 0x7fffffff : len);
             lcu[pos] = j;
         }
         S += __popcll(m);
         T += wave_sum64(kept ? len : 0);
         N += wave_sum64(kept ? (int64_t)C : 0);
     }
+    longest = wave_max64(longest);
+    if (capacity == 0) capacity = (int)(longest > 0x7fffffffLL ? 0x7fffffff : longest);   // L_max = longest item
     int status = 0;
-    if (__any(bad)) status = 1;
+    if (__any(bad) || longest > (int64_t)capacity) status = 1;
     else if (N > loss_pos_capacity) status = 2;
     else if (T > 0x7fffffffLL) status = 3;
     if (status != 0) {
         if (lane == 0) {
             meta[0] = 0; meta[1] = 0; meta[2] = 0; meta[3] = status;
-            meta[4] = 0; meta[5] = 0; meta[6] = 0; meta[7] = 0;
+            meta[4] = 0; meta[5] = capacity; meta[6] = 0; meta[7] = 0;
             row_ptr[0] = 0; cu[0] = 0; lcu[0] = 0;
         }
         return;
@@ -68,9 +81,34 @@ __global__ __launch_bounds__(WAVE) void pack_kernel(
     if (lane == 0) row_ptr[0] = 0;
     while (pos < S) {
         int rem = capacity;
+        if (policy == DPPO_PACK_BEST_FIT) {
+            // longest pool item that fits, oldest among equals; repeat until none fits
+            while (true) {
+                int64_t best = -1;
+                for (int i0 = lo; i0 < next; i0 += WAVE) {
+                    int i = i0 + lane;
+                    int len = (i < next) ? ((volatile const int32_t*)cu)[i] : -1;
+                    if (len > 0 && len <= rem) {
+                        int64_t key = ((int64_t)len << 32) | (int64_t)(0x7fffffff - i);
+                        best = key > best ? key : best;
+                    }
+                }
+                best = wave_max64(best);
+                if (best < 0) break;
+                const int sel = 0x7fffffff - (int)(best & 0xffffffffLL);
+                if (lane == 0) {
+                    order[pos] = lcu[sel];
+                    cu[sel] = -1;
+                }
+                __syncthreads();   // the mark must be visible to the next scan
+                rem -= (int)(best >> 32);
+                pos += 1;
+                if (next < S) next += 1;
+            }
+        } else
         for (int i0 = lo; i0 < next; i0 += WAVE) {
             int i = i0 + lane;
-            int len = (i < S) ? cu[i] : -1;          // -1: placed or past the end
+            int len = (i < S) ? ((volatile const int32_t*)cu)[i] : -1;   // -1: placed or past the end
             int orig = (i < S) ? lcu[i] : 0;
             uint64_t done = 0;                        // lanes already passed by the scan
             while (true) {
@@ -96,7 +134,7 @@ __global__ __launch_bounds__(WAVE) void pack_kernel(
         // advance lo past the placed prefix
         while (lo < S) {
             int i = lo + lane;
-            bool unplaced = (i < S) && cu[i] > 0;
+            bool unplaced = (i < S) && ((volatile const int32_t*)cu)[i] > 0;
             uint64_t m = __ballot(unplaced);
             if (m != 0) { lo += __ffsll((unsigned long long)m) - 1; break; }
             lo += WAVE;
@@ -112,7 +150,7 @@ __global__ __launch_bounds__(WAVE) void pack_kernel(
         int s = s0 + lane;
         int j = (s < S) ? order[s] : 0;
         int P = (s < S) ? prompt_len[j] : 0;
-        int C = (s < S) ? comp_len[j] : 0;
+        int C = (s < S && comp_len != nullptr) ? comp_len[j] : 0;
         int64_t a = (int64_t)P + C, b = C;
         for (int off = 1; off < WAVE; off <<= 1) {   // inclusive scan over the wave
             int64_t ta = __shfl_up(a, off, WAVE), tb = __shfl_up(b, off, WAVE);
@@ -127,7 +165,7 @@ __global__ __launch_bounds__(WAVE) void pack_kernel(
     }
     if (lane == 0) {
         meta[0] = rows; meta[1] = (int32_t)T; meta[2] = (int32_t)N; meta[3] = 0;
-        meta[4] = S; meta[5] = 0; meta[6] = 0; meta[7] = 0;
+        meta[4] = S; meta[5] = capacity; meta[6] = 0; meta[7] = 0;
     }
 }
 
@@ -155,8 +193,9 @@ __global__ void gather_f32_kernel(int64_t n, const int32_t* __restrict__ idx, co
 void launch_pack(const dppo_pack_params& p, const int32_t* prompt_len, const int32_t* comp_len,
                  const uint8_t* keep, int32_t* order, int32_t* row_ptr, int32_t* cu, int32_t* lcu,
                  int32_t* loss_pos, int64_t loss_pos_capacity, int32_t* meta, hipStream_t st) {
-    pack_kernel<<<1, WAVE, 0, st>>>(p.n_items, p.capacity, p.n_win, prompt_len, comp_len, keep, order, row_ptr,
-                                    cu, lcu, loss_pos_capacity, meta);
+    pack_kernel<<<1, WAVE, 0, st>>>(p.n_items, p.capacity, p.n_win, p.policy, prompt_len, comp_len, keep, order,
+                                    row_ptr, cu, lcu, loss_pos_capacity, meta);
+    if (comp_len == nullptr) return;   // prompts alone: no loss positions
     int blocks = p.n_items < 2048 ? p.n_items : 2048;
     loss_pos_kernel<<<blocks, 256, 0, st>>>(meta, order, prompt_len, cu, lcu, loss_pos);
 }

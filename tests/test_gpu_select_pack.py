@@ -114,11 +114,12 @@ def test_select_rejects_bad_arguments(lib):
         lib.dppo_select(np.zeros((2, 1), np.float32), None, None, None, 0.5, 0.5, std_ddof=1, device=DEV)
 
 
-def _cmp_pack(P, pl, cl, keep, cap, n_win):
-    ref = O.pack(pl, cl, keep, cap, n_win)
-    got = P.dppo_pack(pl, cl, keep, cap, n_win, device=DEV)
+def _cmp_pack(P, pl, cl, keep, cap, n_win, policy="first_fit"):
+    ref = O.pack(pl, cl, keep, cap, n_win, policy=policy)
+    got = P.dppo_pack(pl, cl, keep, cap, n_win, device=DEV, policy=policy)
     assert got["device_status"] == 0
     assert (got["n_rows"], got["T"], got["N"], got["S"]) == (ref["n_rows"], ref["T"], ref["N"], ref["S"])
+    assert got["capacity"] == ref["capacity"] and got["density"] == pytest.approx(ref["density"], rel=1e-12)
     for k in ("order", "row_ptr", "cu_seqlens", "loss_cu", "loss_pos"):
         assert np.array_equal(got[k].cpu().numpy(), ref[k]), k
     return ref
@@ -132,6 +133,9 @@ def test_pack_matches_oracle_on_workloads(lib, name):
     n = int(keep.sum())
     for n_win in sorted({1, 2, wl.n_win, 64, 65, n, n + 3}):
         ref = _cmp_pack(lib, rb.item_prompt_len, rb.item_comp_len, keep, wl.capacity, n_win)
+        if n_win <= 1000:      # the oracle's best-fit scan is quadratic in the pool
+            bf = _cmp_pack(lib, rb.item_prompt_len, rb.item_comp_len, keep, wl.capacity, n_win, policy="best_fit")
+            assert bf["T"] == ref["T"]
     assert ref["T"] > 0
     _cmp_pack(lib, rb.item_prompt_len, rb.item_comp_len, None, wl.capacity, wl.n_win)
 
@@ -150,11 +154,32 @@ def test_pack_edge_cases(lib):
             keep[0] = 1
         for n_win in (1, 2, 7, 64, 130, n + 1):
             _cmp_pack(lib, pl, cl, keep, cap, n_win)
+            _cmp_pack(lib, pl, cl, keep, cap, n_win, policy="best_fit")
+            if trial % 5 == 0:
+                _cmp_pack(lib, pl + cl, None, keep, (0, cap)[trial % 2], n_win, policy=("first_fit", "best_fit")[n_win % 2])
     # one-token prompts and completions
     _cmp_pack(lib, np.ones(100, np.int32), np.ones(100, np.int32), None, 7, 5)
     # everything pruned: empty result, no error
     got = lib.dppo_pack(np.array([3, 4], np.int32), np.array([2, 2], np.int32), np.zeros(2, np.uint8), 16, 4, device=DEV)
     assert (got["n_rows"], got["T"], got["N"], got["S"], got["device_status"]) == (0, 0, 0, 0, 0)
+
+
+@pytest.mark.parametrize("name", list(WL.PROMPT_DATASETS))
+def test_pack_whole_prompt_dataset(lib, name):
+    # Sec. 4.3 as the paper uses it: prompts alone, the whole dataset as the stream, L_max = longest prompt
+    pl = WL.make_prompt_dataset(name)
+    dens = {}
+    for policy in ("first_fit", "best_fit"):
+        for n_win in (1, 64, 256, 1000) + ((len(pl),) if policy == "first_fit" else ()):
+            ref = _cmp_pack(lib, pl, None, None, 0, n_win, policy=policy)
+            assert ref["capacity"] == int(pl.max()) and ref["N"] == 0
+            dens[policy, n_win] = ref["density"]
+    # a wider pool never hurts much and the dense packing beats one prompt per slot by far
+    assert dens["first_fit", 256] > dens["first_fit", 1] > float(pl.mean()) / float(pl.max())
+    assert dens["best_fit", 1000] > 0.95
+    # with an explicit capacity and a keep mask
+    keep = (np.arange(len(pl)) % 3 != 0).astype(np.uint8)
+    _cmp_pack(lib, pl, None, keep, 4096, 128, policy="best_fit")
 
 
 def test_pack_reports_device_detected_errors(lib):
@@ -172,6 +197,11 @@ def test_pack_reports_device_detected_errors(lib):
     assert got["device_status"] == 2
     with pytest.raises(lib.DppoError):
         lib.dppo_pack(np.array([3], np.int32), np.array([2], np.int32), None, 16, 0, device=DEV)
+    # prompts alone: a prompt longer than an explicit capacity, an empty prompt
+    got = lib.dppo_pack(np.array([3, 9], np.int32), None, None, 8, 4, device=DEV)
+    assert got["device_status"] == 1
+    got = lib.dppo_pack(np.array([3, 0], np.int32), None, None, 0, 4, device=DEV)
+    assert got["device_status"] == 1
 
 
 def test_gather_puts_weights_in_packed_order(lib):

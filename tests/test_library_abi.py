@@ -49,10 +49,14 @@ def test_host_side_validation_launches_nothing(lib):
     assert lib.dppo_select(ctypes.byref(sp), *([one] * 12), None) == 2
     sp = SelectParams(4, 4, 0.5, 0.5, 1e-6, 1, 0.5, 0, 1)
     assert lib.dppo_select(ctypes.byref(sp), None, *([one] * 11), None) == 1
-    pp = PackParams(0, 16, 4)
+    pp = PackParams(0, 16, 4, 0)
     assert lib.dppo_pack(ctypes.byref(pp), *([one] * 8), 10, one, None) == 2
-    pp = PackParams(4, 16, 0)
+    pp = PackParams(4, 16, 0, 0)
     assert lib.dppo_pack(ctypes.byref(pp), *([one] * 8), 10, one, None) == 1
+    pp = PackParams(4, 16, 4, 7)                          # unknown policy
+    assert lib.dppo_pack(ctypes.byref(pp), *([one] * 8), 10, one, None) == 1
+    pp = PackParams(4, 1, 4, 0)                           # capacity below a 1+1 token item
+    assert lib.dppo_pack(ctypes.byref(pp), *([one] * 8), 10, one, None) == 3
     hs = HeadShape(100, 50, 72, 1000, 1)                  # bf16 needs D % 64 == 0
     assert lib.dppo_token_logprob(ctypes.byref(hs), *([one] * 7), 1 << 20, None) == 5
     assert lib.dppo_workspace_bytes(ctypes.byref(hs), 1) == 0

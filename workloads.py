@@ -128,6 +128,23 @@ def make_rollout(name: str, seed: Optional[int] = None) -> RolloutBatch:
                         u_prompt, u_comp, {"reward_p": p})
 
 
+# Prompt-length sets for packing a whole dataset before any rollout (Sec. 4.3). The sizes are
+# those of the paper's two training sets (8.5 K and 7.5 K problems); the lengths are synthetic:
+# log-normal token counts, short word problems and longer competition problems.
+PROMPT_DATASETS: Dict[str, Tuple] = {
+    "short_8k5": (8500, ("lognormal", 90.0, 0.35, 16, 512)),
+    "long_7k5": (7500, ("lognormal", 140.0, 0.6, 16, 2048)),
+}
+
+
+def make_prompt_dataset(name: str, seed: Optional[int] = None) -> np.ndarray:
+    n, spec = PROMPT_DATASETS[name]
+    if seed is None:
+        seed = list(PROMPT_DATASETS).index(name) + 1
+    rng = np.random.default_rng([seed, 0xDA7A])
+    return _draw_comp_len(rng, spec, n).astype(np.int32)
+
+
 def zipf_table(V: int, exponent: float, seed: int):
     """CDF over ranks (p_r ~ r^-exponent, r=1..V) and a fixed rank->id permutation."""
     w = np.arange(1, V + 1, dtype=np.float64) ** (-exponent)
