@@ -82,7 +82,7 @@ int32_t round_up32(int64_t x, int32_t a) { return (int32_t)((x + a - 1) / a * a)
 void layout(const dppo_head_shape& s, bool bwd, int32_t n_cp, WsPlan& p) {
     p.es = s.dtype == 1 ? 2 : 4;
     p.zs = p.es;
-    p.Vp = round_up32(s.V, 64);
+    p.Vp = round_up32(s.V, mfma_vocab_tile());   // whole vocabulary tiles: the logits epilogue stores unconditionally
     p.n_tiles = s.dtype == 1 ? mfma_logits_row_tiles(s.V) : 0;
     p.n_cp = n_cp;
     const bool need_z = bwd || s.dtype == 0;
@@ -155,7 +155,7 @@ struct Regions {
 
 // Forward statistics of one chunk: Hc (and HcT), targets, log-probs, lse. Leaves the chunk's
 // logits in the workspace when keep_z is set (always for float32).
-void chunk_forward(const dppo_head_shape& s, const WsPlan& p, char* ws, const void* H, const void* W,
+int chunk_forward(const dppo_head_shape& s, const WsPlan& p, char* ws, const void* H, const void* W,
                    const int32_t* ids, const int32_t* loss_pos, ChunkView cv, bool bwd, bool keep_z,
                    float* logp_all, float* lse_all, hipStream_t st) {
     void* Hc = ws + p.o_hc;
@@ -168,7 +168,9 @@ void chunk_forward(const dppo_head_shape& s, const WsPlan& p, char* ws, const vo
         float2* part = reinterpret_cast<float2*>(ws + p.o_part);
         {
             StageTimer tm(DPPO_STAGE_LOGITS_GEMM, st);
-            launch_mfma_logits(W, s.V, s.D, Hc, cv.n_cp, part, keep_z ? ws + p.o_zg : nullptr, p.Vp, p.Vp, st);
+            const int rc = launch_mfma_logits(W, s.V, s.D, Hc, cv.n_cp, part, keep_z ? ws + p.o_zg : nullptr, p.Vp,
+                                              p.Vp, st);
+            if (rc != DPPO_OK) return rc;
         }
         launch_target_logit(1, Hc, W, y, cv.n_cp, s.D, zy, st);
         launch_combine_logprob(part, p.n_tiles, zy, cv, lse_c, logp_all, lse_all, st);
@@ -179,6 +181,7 @@ void chunk_forward(const dppo_head_shape& s, const WsPlan& p, char* ws, const vo
         launch_row_stats_f32(reinterpret_cast<const float*>(ws + p.o_zg), p.Vp, s.V, y, cv, lse_c, logp_all,
                              lse_all, st);
     }
+    return DPPO_OK;
 }
 
 }  // namespace
@@ -321,7 +324,7 @@ int dppo_token_logprob(const dppo_head_shape* shape, const void* H, const void* 
         cv.n0 = n0;
         cv.n_c = (int32_t)((s.N - n0) < p.n_cp ? (s.N - n0) : p.n_cp);
         cv.n_cp = round_up32(cv.n_c, CHUNK_ALIGN);
-        chunk_forward(s, p, w, H, W, ids, loss_pos, cv, false, false, logp, lse, st);
+        if (int rc = chunk_forward(s, p, w, H, W, ids, loss_pos, cv, false, false, logp, lse, st)) return rc;
     }
     return check_launch("dppo_token_logprob");
 }
@@ -371,7 +374,7 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
         cv.n_c = (int32_t)((s.N - n0) < p.n_cp ? (s.N - n0) : p.n_cp);
         cv.n_cp = round_up32(cv.n_c, CHUNK_ALIGN);
         const bool recompute = lp->recompute_logits != 0;
-        chunk_forward(s, p, w, H, W, ids, loss_pos, cv, true, !recompute, logp_all, nullptr, st);
+        if (int rc = chunk_forward(s, p, w, H, W, ids, loss_pos, cv, true, !recompute, logp_all, nullptr, st)) return rc;
 
         TokenLossArgs ta;
         ta.loss_cu = loss_cu; ta.S = S; ta.seq_adv = seq_adv; ta.seq_coef = seq_coef;

@@ -103,9 +103,11 @@ void launch_gemm_plain_f32(const float* A, int64_t lda, const float* B, int64_t 
 int mfma_setup();   // one-time kernel attribute setup, returns dppo status
 // Vocabulary GEMM: rows = vocabulary entries (A = W[V,D]), columns = tokens (B = Hc[n_cp,D]).
 // Writes per-(row tile, token) partial (max, sum exp) to part[tile*n_cp + n]; if Z16 != NULL also
-// stores the logits as fp16 to Z16[n*ldz + v] for v < Vp.
+// stores the logits as fp16 to Z16[n*ldz + v] for v < Vp; Vp must then be a multiple of
+// mfma_vocab_tile() (whole tiles are stored) and ldz >= Vp. Returns a dppo status.
 int32_t mfma_logits_row_tiles(int32_t V);
-void launch_mfma_logits(const void* W, int32_t V, int32_t D, const void* Hc, int32_t n_cp,
+int32_t mfma_vocab_tile();
+int launch_mfma_logits(const void* W, int32_t V, int32_t D, const void* Hc, int32_t n_cp,
                         float2* part, void* Z16, int64_t ldz, int32_t Vp, hipStream_t st);
 // Same GEMM, but the epilogue turns logits straight into gradient entries
 // G[n,v] = c[n] (1[v==y[n]] - exp(z - lse[n])) written as bf16 to G[n*ldg+v] and GT[v*n_cp+n].

@@ -48,16 +48,22 @@ int mfma_setup() {
 }
 
 int32_t mfma_logits_row_tiles(int32_t V) { return (int32_t)ceil_div(V, CfgBig::BM); }
+int32_t mfma_vocab_tile() { return CfgBig::BM; }
 
-void launch_mfma_logits(const void* W, int32_t V, int32_t D, const void* Hc, int32_t n_cp, float2* part,
+int launch_mfma_logits(const void* W, int32_t V, int32_t D, const void* Hc, int32_t n_cp, float2* part,
                         void* Z16, int64_t ldz, int32_t Vp, hipStream_t st) {
     if (Z16) {
+        // the epilogue stores whole tiles: the caller pads the row pitch to whole vocabulary tiles
+        if (Vp % CfgBig::BM != 0 || ldz < Vp || Vp < V)
+            return fail(DPPO_ERR_UNSUPPORTED, "logits buffer not padded to whole vocabulary tiles (Vp %d, pitch %lld)", Vp,
+                        (long long)ldz);
         EpiLogits<true> e{part, n_cp, reinterpret_cast<_Float16*>(Z16), ldz, Vp};
         launch<CfgBig>(W, D, Hc, D, V, n_cp, D, e, st);
     } else {
         EpiLogits<false> e{part, n_cp, nullptr, 0, 0};
         launch<CfgBig>(W, D, Hc, D, V, n_cp, D, e, st);
     }
+    return DPPO_OK;
 }
 
 void launch_mfma_logits_grad(const void* W, int32_t V, int32_t D, const void* Hc, int32_t n_cp,

@@ -164,12 +164,15 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
     const int a_base = (wave_m * Cfg::WTM + frag_row) * ROWB;
     const int b_base = Cfg::A_BYTES + (wave_n * Cfg::WTN + frag_row) * ROWB;
     bf16x8 af[2][MI], bfr[2][NI];
+    auto read_a = [&](int set, const char* st, int kk, int mi) {
+        const int kc_off = ((kk * 2 + frag_half) ^ sw) << 4;
+        af[set][mi] = *reinterpret_cast<const bf16x8*>(st + a_base + mi * 32 * ROWB + kc_off);
+    };
     auto read_frags = [&](int set, int buf, int kk) {
         const char* st = smem + buf * Cfg::STAGE_BYTES;
         const int kc_off = ((kk * 2 + frag_half) ^ sw) << 4;
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-            af[set][mi] = *reinterpret_cast<const bf16x8*>(st + a_base + mi * 32 * ROWB + kc_off);
+        for (int mi = 0; mi < MI; ++mi) read_a(set, st, kk, mi);
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni)
             bfr[set][ni] = *reinterpret_cast<const bf16x8*>(st + b_base + ni * 32 * ROWB + kc_off);
@@ -178,7 +181,7 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
     auto read_one = [&](int set, int buf, int kk, bool isA, int idx) {
         const char* st = smem + buf * Cfg::STAGE_BYTES;
         const int kc_off = ((kk * 2 + frag_half) ^ sw) << 4;
-        if (isA) af[set][idx] = *reinterpret_cast<const bf16x8*>(st + a_base + idx * 32 * ROWB + kc_off);
+        if (isA) read_a(set, st, kk, idx);
         else bfr[set][idx] = *reinterpret_cast<const bf16x8*>(st + b_base + idx * 32 * ROWB + kc_off);
     };
 
@@ -316,32 +319,6 @@ struct EpiLogits {
     __device__ __forceinline__ void run(f32x16 (&acc)[Cfg::MI][Cfg::NI], const TileCtx& c) const {
         constexpr int MI = Cfg::MI, NI = Cfg::NI;
         const float NEG_INF = -__builtin_inff();
-        float mx[NI], sm[NI];
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni) {
-            float m = NEG_INF;
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const int row = c.m0 + mi * 32 + acc_row(c.lane, j);
-                    const float v = row < c.M ? acc[mi][ni][j] : NEG_INF;
-                    m = fmaxf(m, v);
-                }
-            m = fmaxf(m, __shfl_xor(m, 32, 64));
-            const float mref = (m == NEG_INF) ? 0.0f : m;
-            float s = 0.0f;
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const int row = c.m0 + mi * 32 + acc_row(c.lane, j);
-                    const float e = __builtin_amdgcn_exp2f((acc[mi][ni][j] - mref) * LOG2E);
-                    s += row < c.M ? e : 0.0f;
-                }
-            s += __shfl_xor(s, 32, 64);
-            mx[ni] = m; sm[ni] = s;
-        }
         // LDS (free after the main loop's closing barrier): the tile's logits as fp16, laid out
         // [token][vocabulary row] so that they leave as 16-byte stores of whole 512-byte row pieces,
         // then the per-wavefront (max, sum) pairs of the WGM wavefronts that share a token.
@@ -366,27 +343,66 @@ struct EpiLogits {
                         *reinterpret_cast<f16x4*>(c.smem + tok * ZPITCH + vloc * 2) = h;
                     }
             }
+            __syncthreads();
         }
+        // per-lane running max over this wavefront's vocabulary rows, per token column
+        float mx[NI], mref[NI], sm[NI];
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+            float m = NEG_INF;
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const int row = c.m0 + mi * 32 + acc_row(c.lane, j);
+                    const float v = row < c.M ? acc[mi][ni][j] : NEG_INF;
+                    m = fmaxf(m, v);
+                }
+            m = fmaxf(m, __shfl_xor(m, 32, 64));
+            mx[ni] = m;
+            mref[ni] = (m == NEG_INF) ? 0.0f : m;
+            sm[ni] = 0.0f;
+        }
+        // The store path of a compute unit takes a 1 KB store instruction only every few dozen
+        // cycles, so the 16-byte stores of the staged tile (32 lanes x 16 bytes = one 512-byte token
+        // row piece, two rows per instruction) are interleaved with the exponentials of the sum:
+        // the arithmetic runs while the store queue drains.
+        constexpr int CH = Cfg::BM / 8;                     // 16-byte chunks per row
+        constexpr int ROWS_PER_PASS = Cfg::NT / CH;
+        constexpr int PASSES = Cfg::BN / ROWS_PER_PASS;
+        constexpr int TERMS = MI * NI * 16;                 // exponentials per lane
+        static_assert(TERMS % PASSES == 0, "terms per store pass");
+        constexpr int TPP = TERMS / PASSES;
+        const int ch = c.tid % CH;
+        const int v0 = c.bm0 + ch * 8;
+        // Vp is a multiple of BM (checked by the launcher), so every column of the tile has a home in
+        // Z16 and the stores need no branch, which would undo the interleaving.
+#pragma unroll
+        for (int it = 0; it < PASSES; ++it) {
+            if (STORE_Z) {
+                const int r = c.tid / CH + it * ROWS_PER_PASS;
+                const u32x4 val = *reinterpret_cast<const u32x4*>(c.smem + r * ZPITCH + ch * 16);
+                *reinterpret_cast<u32x4*>(Z16 + (int64_t)(c.bn0 + r) * ldz + v0) = val;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int e = 0; e < TPP; ++e) {
+                const int idx = it * TPP + e;
+                const int ni = idx / (MI * 16), mi = (idx / 16) % MI, j = idx % 16;
+                const int row = c.m0 + mi * 32 + acc_row(c.lane, j);
+                const float ex = __builtin_amdgcn_exp2f((acc[mi][ni][j] - mref[ni]) * LOG2E);
+                sm[ni] += row < c.M ? ex : 0.0f;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) sm[ni] += __shfl_xor(sm[ni], 32, 64);
         if (c.lane < 32) {
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni)
                 red[c.wave_m * Cfg::BN + c.wave_n * Cfg::WTN + ni * 32 + c.lane] = make_float2(mx[ni], sm[ni]);
         }
         __syncthreads();
-        if (STORE_Z) {
-            // 32 lanes x 16 bytes = one 512-byte token row of the tile; two rows per instruction
-            constexpr int CH = Cfg::BM / 8;                     // 16-byte chunks per row
-            constexpr int ROWS_PER_PASS = Cfg::NT / CH;
-            const int ch = c.tid % CH;
-            const int v0 = c.bm0 + ch * 8;
-            if (v0 < Vp) {
-#pragma unroll 4
-                for (int r = c.tid / CH; r < Cfg::BN; r += ROWS_PER_PASS) {
-                    const u32x4 val = *reinterpret_cast<const u32x4*>(c.smem + r * ZPITCH + ch * 16);
-                    *reinterpret_cast<u32x4*>(Z16 + (int64_t)(c.bn0 + r) * ldz + v0) = val;
-                }
-            }
-        }
         for (int t = c.tid; t < Cfg::BN; t += Cfg::NT) {
             float m = NEG_INF;
 #pragma unroll
