@@ -100,7 +100,7 @@ void layout(const dppo_head_shape& s, bool bwd, int32_t n_cp, WsPlan& p) {
     p.o_hct = take(bwd ? (size_t)n_cp * s.D * p.es : 0);
     p.o_part = take((size_t)p.n_tiles * n_cp * 8);
     p.o_zg = take(need_z ? (size_t)n_cp * p.Vp * p.zs : 0);
-    p.o_gt = take(bwd ? (size_t)n_cp * p.Vp * p.zs : 0);
+    p.o_gt = take(bwd && s.dtype == 0 ? (size_t)n_cp * p.Vp * p.zs : 0);   // transposed copy: float32 path only
     p.o_y = take((size_t)n_cp * 4);
     p.o_zy = take((size_t)n_cp * 4);
     p.o_lse = take((size_t)n_cp * 4);
@@ -390,29 +390,32 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
         void* GT = w + p.o_gt;
         if (recompute) {
             StageTimer tm(DPPO_STAGE_LOGITS_GEMM, st);
-            launch_mfma_logits_grad(W, s.V, s.D, w + p.o_hc, cv.n_cp, y, lse_c, ta.c_chunk, G, GT, p.Vp, p.Vp, st);
+            const int rc2 = launch_mfma_logits_grad(W, s.V, s.D, w + p.o_hc, cv.n_cp, y, lse_c, ta.c_chunk, G, p.Vp,
+                                                    p.Vp, st);
+            if (rc2 != DPPO_OK) return rc2;
         } else {
             StageTimer tm(DPPO_STAGE_GRAD_LOGITS, st);
             launch_grad_logits(s.dtype, G, GT, s.V, p.Vp, y, lse_c, ta.c_chunk, cv.n_cp, st);
         }
 
         // dH rows of the chunk: G[n_c, Vp] * WT[D, Vp]^T, scattered to the loss rows of dH
+        // (bf16: G is in the blocked chunk layout and serves both GEMMs; float32: row-major G and GT)
         StoreSpec oh;
         oh.out_bf16 = s.dtype == 1; oh.accumulate = 0; oh.ldc = s.D;
         if (loss_pos) { oh.C = dH; oh.row_map = loss_pos; oh.row_base = n0; }
         else { oh.C = reinterpret_cast<char*>(dH) + (size_t)n0 * s.D * p.es; oh.row_map = nullptr; oh.row_base = 0; }
-        // dW: GT[V, n_cp] * HcT[D, n_cp]^T
+        // dW[v, d] (+)= sum_n G[n, v] HcT[d, n]
         StoreSpec ow;
         ow.C = dW; ow.ldc = s.D; ow.out_bf16 = 0; ow.accumulate = (first && !lp->accumulate_dW) ? 0 : 1;
         ow.row_map = nullptr; ow.row_base = 0;
         if (s.dtype == 1) {
             {
                 StageTimer tm(DPPO_STAGE_DH_GEMM, st);
-                launch_mfma_gemm(G, p.Vp, w + p.o_wt, p.Vp, cv.n_c, s.D, p.Vp, oh, st);
+                launch_mfma_dh(G, p.Vp, w + p.o_wt, cv.n_c, s.D, oh, st);
             }
             {
                 StageTimer tm(DPPO_STAGE_DW_GEMM, st);
-                launch_mfma_gemm(GT, cv.n_cp, w + p.o_hct, cv.n_cp, s.V, s.D, cv.n_cp, ow, st);
+                launch_mfma_dw(G, p.Vp, w + p.o_hct, cv.n_cp, s.V, s.D, ow, st);
             }
         } else {
             launch_gemm_plain_f32(reinterpret_cast<const float*>(G), p.Vp, reinterpret_cast<const float*>(w + p.o_wt),

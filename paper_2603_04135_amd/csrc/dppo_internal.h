@@ -70,8 +70,10 @@ struct TokenLossArgs {
 void launch_token_loss(const TokenLossArgs& a, ChunkView cv, hipStream_t st);
 
 // In place over the chunk's stored logits: G[n,v] = c[n] (1[v==y[n]] - exp(z - lse[n])) for
-// v < V, 0 for V <= v < Vp; also written transposed to GT[Vp, n_cp].
-// dtype 1: Z is fp16 and G, GT are bf16; dtype 0: all float.
+// v < V, 0 for V <= v < Vp.
+// dtype 0: all float, row-major [n_cp, Vp], also written transposed to GT[Vp, n_cp].
+// dtype 1: Z is fp16 and G bf16, both in the blocked chunk layout of the MFMA GEMMs (64 x 256
+// element blocks, Vp a multiple of 256); GT is not used.
 void launch_grad_logits(int dtype, void* ZG, void* GT, int32_t V, int32_t Vp, const int32_t* y,
                         const float* lse, const float* c, int32_t n_cp, hipStream_t st);
 
@@ -103,19 +105,24 @@ void launch_gemm_plain_f32(const float* A, int64_t lda, const float* B, int64_t 
 int mfma_setup();   // one-time kernel attribute setup, returns dppo status
 // Vocabulary GEMM: rows = vocabulary entries (A = W[V,D]), columns = tokens (B = Hc[n_cp,D]).
 // Writes per-(row tile, token) partial (max, sum exp) to part[tile*n_cp + n]; if Z16 != NULL also
-// stores the logits as fp16 to Z16[n*ldz + v] for v < Vp; Vp must then be a multiple of
-// mfma_vocab_tile() (whole tiles are stored) and ldz >= Vp. Returns a dppo status.
+// stores the chunk's logits as fp16 to Z16, a [n_cp, ldz] matrix in the blocked chunk layout
+// (blocks of 64 tokens x 256 vocabulary entries, each contiguous; block (i, j) at element
+// i * 64 * ldz + j * 16384). ldz = Vp must then be a multiple of mfma_vocab_tile() (whole tiles
+// are stored). Returns a dppo status.
 int32_t mfma_logits_row_tiles(int32_t V);
 int32_t mfma_vocab_tile();
 int launch_mfma_logits(const void* W, int32_t V, int32_t D, const void* Hc, int32_t n_cp,
                         float2* part, void* Z16, int64_t ldz, int32_t Vp, hipStream_t st);
 // Same GEMM, but the epilogue turns logits straight into gradient entries
-// G[n,v] = c[n] (1[v==y[n]] - exp(z - lse[n])) written as bf16 to G[n*ldg+v] and GT[v*n_cp+n].
-void launch_mfma_logits_grad(const void* W, int32_t V, int32_t D, const void* Hc, int32_t n_cp,
-                             const int32_t* y, const float* lse, const float* c, void* G, void* GT,
-                             int64_t ldg, int32_t Vp, hipStream_t st);
-// Generic C = A B^T with a plain store epilogue.
-void launch_mfma_gemm(const void* A, int64_t lda, const void* B, int64_t ldb, int32_t M, int32_t N,
-                      int32_t K, const StoreSpec& out, hipStream_t st);
+// G[n,v] = c[n] (1[v==y[n]] - exp(z - lse[n])) written as bf16 to the blocked chunk G (pitch ldg = Vp).
+int launch_mfma_logits_grad(const void* W, int32_t V, int32_t D, const void* Hc, int32_t n_cp,
+                            const int32_t* y, const float* lse, const float* c, void* G, int64_t ldg,
+                            int32_t Vp, hipStream_t st);
+// dH rows of a chunk: C[n_c, D] = G[n_c, Vp] WT[D, Vp]^T with G in the blocked chunk layout (pitch Vp).
+void launch_mfma_dh(const void* G, int32_t Vp, const void* WT, int32_t n_c, int32_t D, const StoreSpec& out,
+                    hipStream_t st);
+// dW of a chunk: C[V, D] (+)= G^T HcT^T = sum_n G[n, v] HcT[d, n], G read k-major from the same blocks.
+void launch_mfma_dw(const void* G, int32_t Vp, const void* HcT, int32_t n_cp, int32_t V, int32_t D,
+                    const StoreSpec& out, hipStream_t st);
 
 }  // namespace dppo

@@ -6,7 +6,7 @@ namespace {
 using namespace mfma;
 
 // 256x256x64 tile, 2x4 wavefronts (128x64 each), 2 slices in flight, loads spread over 2 k-steps,
-// bands of 4 tile rows.
+// bands of 4 tile rows. The blocked chunk layout (64 x 256 element blocks) is tied to this tile.
 typedef PipeCfg<256, 256, 64, 2, 4, 2, 3, 2, 4> CfgBig;
 
 // Dynamic LDS of a kernel: the operand slices, or the epilogue's staging area if that is larger.
@@ -17,18 +17,18 @@ constexpr int lds_request() {
     return Cfg::LDS_BYTES > e ? Cfg::LDS_BYTES : e;
 }
 
-template <class Cfg, class Epi>
+template <class Cfg, int AM = A_ROWS, class Epi>
 void launch(const void* A, int64_t lda, const void* B, int64_t ldb, int M, int N, int K, const Epi& epi,
             hipStream_t st) {
     const int tiles_m = (int)ceil_div(M, Cfg::BM), tiles_n = (int)ceil_div(N, Cfg::BN);
-    gemm_nt_kernel<Cfg, Epi><<<dim3(tiles_m * tiles_n), dim3(Cfg::NT), lds_request<Cfg, Epi>(), st>>>(
+    gemm_nt_kernel<Cfg, Epi, AM><<<dim3(tiles_m * tiles_n), dim3(Cfg::NT), lds_request<Cfg, Epi>(), st>>>(
         reinterpret_cast<const uint16_t*>(A), lda, reinterpret_cast<const uint16_t*>(B), ldb, M, N, K, tiles_m,
         tiles_n, epi);
 }
 
-template <class Cfg, class Epi>
+template <class Cfg, class Epi, int AM = A_ROWS>
 hipError_t allow_lds() {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_kernel<Cfg, Epi>),
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_kernel<Cfg, Epi, AM>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_request<Cfg, Epi>());
 }
 
@@ -36,8 +36,8 @@ hipError_t allow_lds() {
 
 int mfma_setup() {
     static int status = [] {
-        hipError_t e = allow_lds<CfgBig, EpiStoreDW>();
-        if (e == hipSuccess) e = allow_lds<CfgBig, EpiStoreDH>();
+        hipError_t e = allow_lds<CfgBig, EpiStoreDW, A_BLK_KM>();
+        if (e == hipSuccess) e = allow_lds<CfgBig, EpiStoreDH, A_BLK_ROWS>();
         if (e == hipSuccess) e = allow_lds<CfgBig, EpiLogits<true>>();
         if (e == hipSuccess) e = allow_lds<CfgBig, EpiLogits<false>>();
         if (e == hipSuccess) e = allow_lds<CfgBig, EpiLogitsGrad>();
@@ -54,7 +54,7 @@ int launch_mfma_logits(const void* W, int32_t V, int32_t D, const void* Hc, int3
                         void* Z16, int64_t ldz, int32_t Vp, hipStream_t st) {
     if (Z16) {
         // the epilogue stores whole tiles: the caller pads the row pitch to whole vocabulary tiles
-        if (Vp % CfgBig::BM != 0 || ldz < Vp || Vp < V)
+        if (Vp % CfgBig::BM != 0 || ldz != Vp || Vp < V)
             return fail(DPPO_ERR_UNSUPPORTED, "logits buffer not padded to whole vocabulary tiles (Vp %d, pitch %lld)", Vp,
                         (long long)ldz);
         EpiLogits<true> e{part, n_cp, reinterpret_cast<_Float16*>(Z16), ldz, Vp};
@@ -66,22 +66,27 @@ int launch_mfma_logits(const void* W, int32_t V, int32_t D, const void* Hc, int3
     return DPPO_OK;
 }
 
-void launch_mfma_logits_grad(const void* W, int32_t V, int32_t D, const void* Hc, int32_t n_cp,
-                             const int32_t* y, const float* lse, const float* c, void* G, void* GT,
-                             int64_t ldg, int32_t Vp, hipStream_t st) {
-    EpiLogitsGrad e{y, lse, c, reinterpret_cast<uint16_t*>(G), reinterpret_cast<uint16_t*>(GT), ldg, n_cp, V, Vp};
+int launch_mfma_logits_grad(const void* W, int32_t V, int32_t D, const void* Hc, int32_t n_cp,
+                            const int32_t* y, const float* lse, const float* c, void* G, int64_t ldg,
+                            int32_t Vp, hipStream_t st) {
+    if (Vp % CfgBig::BM != 0 || ldg != Vp || Vp < V)
+        return fail(DPPO_ERR_UNSUPPORTED, "gradient-logits buffer not padded to whole vocabulary tiles (Vp %d, pitch %lld)",
+                    Vp, (long long)ldg);
+    EpiLogitsGrad e{y, lse, c, reinterpret_cast<uint16_t*>(G), ldg, n_cp, V};
     launch<CfgBig>(W, D, Hc, D, V, n_cp, D, e, st);
+    return DPPO_OK;
 }
 
-void launch_mfma_gemm(const void* A, int64_t lda, const void* B, int64_t ldb, int32_t M, int32_t N, int32_t K,
-                      const StoreSpec& out, hipStream_t st) {
-    if (out.out_bf16) {
-        EpiStoreDH e{nullptr, reinterpret_cast<uint16_t*>(out.C), out.ldc, 0, out.row_map, out.row_base};
-        launch<CfgBig>(A, lda, B, ldb, M, N, K, e, st);
-    } else {
-        EpiStoreDW e{reinterpret_cast<float*>(out.C), nullptr, out.ldc, out.accumulate, nullptr, 0};
-        launch<CfgBig>(A, lda, B, ldb, M, N, K, e, st);
-    }
+void launch_mfma_dh(const void* G, int32_t Vp, const void* WT, int32_t n_c, int32_t D, const StoreSpec& out,
+                    hipStream_t st) {
+    EpiStoreDH e{nullptr, reinterpret_cast<uint16_t*>(out.C), out.ldc, 0, out.row_map, out.row_base};
+    launch<CfgBig, A_BLK_ROWS>(G, Vp, WT, Vp, n_c, D, Vp, e, st);
+}
+
+void launch_mfma_dw(const void* G, int32_t Vp, const void* HcT, int32_t n_cp, int32_t V, int32_t D,
+                    const StoreSpec& out, hipStream_t st) {
+    EpiStoreDW e{reinterpret_cast<float*>(out.C), nullptr, out.ldc, out.accumulate, nullptr, 0};
+    launch<CfgBig, A_BLK_KM>(G, Vp, HcT, n_cp, V, D, n_cp, e, st);
 }
 
 }  // namespace dppo

@@ -32,6 +32,9 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) char lds_char;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int NUM_XCD = 8;
@@ -57,6 +60,15 @@ __device__ __forceinline__ int acc_row(int lane, int j) { return 8 * (j >> 2) + 
 template <int VM>
 __device__ __forceinline__ void wait_loads_then_barrier() {
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(VM) : "memory");
+}
+
+// Transposing LDS read: within each group of 16 lanes, lane i receives element i % 4 of the 8-byte
+// rows addressed by lanes i / 4, 4 + i / 4, 8 + i / 4 and 12 + i / 4. The __restrict__ parameter
+// gives the access an alias scope of its own; without one the compiler assumes that the read may
+// alias the direct-to-LDS loads in flight and drains them all (vmcnt(0)) before every such read.
+// The ordering against those loads is enforced by wait_loads_then_barrier.
+__device__ __forceinline__ s16x4 lds_read_tr16(const lds_char* __restrict__ p) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
 }
 
 // XOR term of the LDS swizzle: logical 16-byte chunk kc of tile row `row` lives at physical chunk
@@ -100,11 +112,32 @@ struct PipeCfg {
     static_assert(MI + NI <= MI * NI && LPSTEP <= MI * NI, "one read / load slot per MFMA of a k-step");
 };
 
-template <class Cfg, class Epi>
+// Layout of the A operand (template parameter AM):
+//   A_ROWS      A is [M, K], K contiguous, lda = row pitch;
+//   A_BLK_ROWS  A is a row-major [M, lda] matrix stored in blocks of BLK_R x BLK_C elements,
+//               element (r, c) at blk_offset(r, c, lda); the GEMM's rows are the matrix rows and
+//               K runs along its columns (the dH GEMM reads the gradient-logits chunk this way);
+//   A_BLK_KM    the same blocked matrix, but the GEMM's K runs along the matrix ROWS and its M
+//               along the columns (the dW GEMM: no transposed copy of the chunk is ever made).
+// In the blocked layout a BK x BM slice of a tile (A_BLK_KM) is one contiguous 32 KB run and the
+// rows of a BM x BK slice (A_BLK_ROWS) stay inside four such runs; a plain [K, M] matrix read tile
+// by tile touches BK widely separated rows per slice and new pages at every slice.
+// A_BLK_KM: the slice sits in LDS as BK rows of BM elements and the MFMA operand (8 consecutive k
+// for one m per lane) is gathered by two transposing reads. The 16-byte chunks of a k-row are
+// XOR-swizzled by 4 * (k & 3) so that the 4 k-rows x 32 bytes a group of 16 lanes touches, and
+// the two groups of a half-wave, fall into different banks.
+enum { A_ROWS = 0, A_BLK_ROWS = 1, A_BLK_KM = 2 };
+constexpr int BLK_R = 64, BLK_C = 256;
+__host__ __device__ __forceinline__ size_t blk_offset(int64_t r, int64_t c, int64_t ld) {
+    return (size_t)(r / BLK_R) * BLK_R * ld + (size_t)(c / BLK_C) * (BLK_R * BLK_C) + (r % BLK_R) * BLK_C + c % BLK_C;
+}
+
+template <class Cfg, class Epi, int AM = A_ROWS>
 __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __restrict__ A, int64_t lda,
                                                           const uint16_t* __restrict__ B, int64_t ldb, int M,
                                                           int N, int K, int tiles_m, int tiles_n, Epi epi) {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
+    constexpr bool A_KM = AM == A_BLK_KM;
     constexpr int MI = Cfg::MI, NI = Cfg::NI, KK = Cfg::KK, STAGES = Cfg::STAGES, LPS = Cfg::LPS;
     constexpr int ROWB = Cfg::ROWB, CPR = Cfg::CPR, LPSTEP = Cfg::LPSTEP, SS = Cfg::SPREAD_STEPS;
 
@@ -138,23 +171,38 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
         const bool isA = i < Cfg::A_LD;
         const int ii = isA ? i : i - Cfg::A_LD;
         const int ci = (ii * Cfg::NW + wave) * 64 + lane;
+        if (A_KM && isA) {
+            static_assert(!A_KM || (Cfg::BK == BLK_R && Cfg::BM == BLK_C), "block shape = slice shape");
+            constexpr int CPR_A = Cfg::BM / 8;
+            const int krow = ci / CPR_A, pc = ci % CPR_A;
+            const int mc = pc ^ (4 * (krow & 3));
+            pl[i] = A + blk_offset(krow, bm0 + mc * 8, lda);
+            continue;
+        }
         const int row = ci / CPR, pc = ci % CPR;
         const int kc = pc ^ swz<CPR, Cfg::SWZ>(row);
         int r = (isA ? bm0 : bn0) + row;
         const int lim = isA ? M : N;
         r = r < lim ? r : lim - 1;
+        if (AM == A_BLK_ROWS && isA) {
+            static_assert(AM != A_BLK_ROWS || BLK_C % Cfg::BK == 0, "a slice stays inside one block column");
+            pl[i] = A + blk_offset(r, kc * 8, lda);
+            continue;
+        }
         pl[i] = (isA ? A : B) + (size_t)r * (isA ? lda : ldb) + kc * 8;
     }
     // issues loads [first, first+count) of slice kt into buffer buf
     auto issue_loads = [&](int buf, int kt, int first, int count) {
         char* dst = smem + buf * Cfg::STAGE_BYTES + wave * 1024;
         const size_t koff = (size_t)kt * Cfg::BK;
+        const size_t koff_a = A_KM ? (size_t)kt * BLK_R * (size_t)lda
+                              : AM == A_BLK_ROWS ? blk_offset(0, (int64_t)kt * Cfg::BK, lda) : koff;
 #pragma unroll
         for (int i = 0; i < LPS; ++i) {
             if (i < first || i >= first + count) continue;
             const bool isA = i < Cfg::A_LD;
             const int ii = isA ? i : i - Cfg::A_LD;
-            __builtin_amdgcn_global_load_lds(DPPO_GPTR(pl[i] + koff),
+            __builtin_amdgcn_global_load_lds(DPPO_GPTR(pl[i] + (isA ? koff_a : koff)),
                                              DPPO_LPTR(dst + (isA ? 0 : Cfg::A_BYTES) + ii * Cfg::NW * 1024), 16, 0, 0);
         }
     };
@@ -164,9 +212,31 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
     const int a_base = (wave_m * Cfg::WTM + frag_row) * ROWB;
     const int b_base = Cfg::A_BYTES + (wave_n * Cfg::WTN + frag_row) * ROWB;
     bf16x8 af[2][MI], bfr[2][NI];
+    // A_KM: byte offset, inside the A slice, of this lane's 8-byte source row for block mi at k-step 0
+    // (first of the two transposing reads; the second is 4 k-rows further on).
+    constexpr int ROWB_A = Cfg::BM * 2;
+    int a_km[MI];
+    if (A_KM) {
+        static_assert(!A_KM || (Cfg::WTM % 128 == 0 && MI <= 4), "swizzle of the [K, M] slice");
+        const int s16 = lane & 15, grp = (lane >> 4) & 1;
+        const int krow = 8 * frag_half + (s16 >> 2);
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            const int chunk = wave_m * (Cfg::WTM / 8) + 4 * (mi ^ (s16 >> 2)) + 2 * grp + ((s16 & 3) >> 1);
+            a_km[mi] = krow * ROWB_A + chunk * 16 + (s16 & 1) * 8;
+        }
+    }
     auto read_a = [&](int set, const char* st, int kk, int mi) {
-        const int kc_off = ((kk * 2 + frag_half) ^ sw) << 4;
-        af[set][mi] = *reinterpret_cast<const bf16x8*>(st + a_base + mi * 32 * ROWB + kc_off);
+        if (A_KM) {
+            const lds_char* p = (const lds_char*)(st + a_km[mi] + kk * 16 * ROWB_A);
+            const s16x4 lo = lds_read_tr16(p);
+            const s16x4 hi = lds_read_tr16(p + 4 * ROWB_A);
+            const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            af[set][mi] = __builtin_bit_cast(bf16x8, v);
+        } else {
+            const int kc_off = ((kk * 2 + frag_half) ^ sw) << 4;
+            af[set][mi] = *reinterpret_cast<const bf16x8*>(st + a_base + mi * 32 * ROWB + kc_off);
+        }
     };
     auto read_frags = [&](int set, int buf, int kk) {
         const char* st = smem + buf * Cfg::STAGE_BYTES;
@@ -313,15 +383,16 @@ constexpr float LOG2E = 1.4426950408889634f;
 template <bool STORE_Z>
 struct EpiLogits {
     float2* part; int64_t n_cp;    // part[tile_m * n_cp + token]
-    _Float16* Z16; int64_t ldz; int Vp;
+    _Float16* Z16; int64_t ldz; int Vp;   // Z16: [n_cp, ldz] in BLK_R x BLK_C blocks (blk_offset)
 
     template <class Cfg>
     __device__ __forceinline__ void run(f32x16 (&acc)[Cfg::MI][Cfg::NI], const TileCtx& c) const {
         constexpr int MI = Cfg::MI, NI = Cfg::NI;
         const float NEG_INF = -__builtin_inff();
         // LDS (free after the main loop's closing barrier): the tile's logits as fp16, laid out
-        // [token][vocabulary row] so that they leave as 16-byte stores of whole 512-byte row pieces,
-        // then the per-wavefront (max, sum) pairs of the WGM wavefronts that share a token.
+        // [token][vocabulary row] so that they leave as 16-byte stores that fill the tile's four
+        // 32 KB blocks of the chunk front to back, then the per-wavefront (max, sum) pairs of the
+        // WGM wavefronts that share a token.
         constexpr int ZPITCH = Cfg::BM * 2 + 16;      // bytes per token row; +16 staggers the banks
         float2* red = reinterpret_cast<float2*>(c.smem + (STORE_Z ? Cfg::BN * ZPITCH : 0));
         if (STORE_Z) {
@@ -375,14 +446,15 @@ struct EpiLogits {
         constexpr int TPP = TERMS / PASSES;
         const int ch = c.tid % CH;
         const int v0 = c.bm0 + ch * 8;
-        // Vp is a multiple of BM (checked by the launcher), so every column of the tile has a home in
-        // Z16 and the stores need no branch, which would undo the interleaving.
+        // ldz is a multiple of BM = BLK_C (checked by the launcher), so every column of the tile has a
+        // home in Z16 and the stores need no branch, which would undo the interleaving.
+        static_assert(!STORE_Z || (Cfg::BM == BLK_C && Cfg::BN % BLK_R == 0), "tile = whole blocks");
 #pragma unroll
         for (int it = 0; it < PASSES; ++it) {
             if (STORE_Z) {
                 const int r = c.tid / CH + it * ROWS_PER_PASS;
                 const u32x4 val = *reinterpret_cast<const u32x4*>(c.smem + r * ZPITCH + ch * 16);
-                *reinterpret_cast<u32x4*>(Z16 + (int64_t)(c.bn0 + r) * ldz + v0) = val;
+                *reinterpret_cast<u32x4*>(Z16 + blk_offset(c.bn0 + r, v0, ldz)) = val;
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -424,16 +496,20 @@ struct EpiLogits {
     }
 };
 
-// Rows = vocabulary entries, columns = tokens: softmax-gradient entries straight from the logits.
+// Rows = vocabulary entries, columns = tokens: softmax-gradient entries straight from the logits,
+// staged through LDS as [token][vocabulary row] and stored to the blocked chunk like the logits.
 struct EpiLogitsGrad {
     const int32_t* y; const float* lse; const float* cvec;
-    uint16_t* G; uint16_t* GT; int64_t ldg; int64_t n_cp; int V, Vp;
+    uint16_t* G; int64_t ldg; int64_t n_cp; int V;
 
     template <class Cfg>
     __device__ __forceinline__ void run(f32x16 (&acc)[Cfg::MI][Cfg::NI], const TileCtx& c) const {
+        static_assert(Cfg::BM == BLK_C && Cfg::BN % BLK_R == 0, "tile = whole blocks");
+        constexpr int ZPITCH = Cfg::BM * 2 + 16;
 #pragma unroll
         for (int ni = 0; ni < Cfg::NI; ++ni) {
-            const int64_t col = c.n0 + ni * 32 + (c.lane & 31);
+            const int tok = c.wave_n * Cfg::WTN + ni * 32 + (c.lane & 31);
+            const int64_t col = c.bn0 + tok;
             const bool col_ok = col < n_cp;
             const int yt = col_ok ? y[col] : -1;
             const float l = col_ok ? lse[col] : 0.0f;
@@ -442,27 +518,33 @@ struct EpiLogitsGrad {
             for (int mi = 0; mi < Cfg::MI; ++mi)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const int v0 = c.m0 + mi * 32 + 8 * g + 4 * (c.lane >> 5);
-                    if (v0 < Vp && col_ok) {
-                        bf16x4 h;
+                    const int vloc = c.wave_m * Cfg::WTM + mi * 32 + 8 * g + 4 * (c.lane >> 5);
+                    bf16x4 h;
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const int v = v0 + q;
-                            const float p = __builtin_amdgcn_exp2f((acc[mi][ni][4 * g + q] - l) * LOG2E);
-                            float gv = cn * ((v == yt ? 1.0f : 0.0f) - p);
-                            gv = v < V ? gv : 0.0f;
-                            const __bf16 b = (__bf16)gv;   // scalar copy: reading h[q] back right after writing it miscompiles
-                            h[q] = b;
-                            GT[(int64_t)v * n_cp + col] = __builtin_bit_cast(uint16_t, b);
-                        }
-                        *reinterpret_cast<bf16x4*>(G + col * ldg + v0) = h;
+                    for (int q = 0; q < 4; ++q) {
+                        const int v = c.bm0 + vloc + q;
+                        const float p = __builtin_amdgcn_exp2f((acc[mi][ni][4 * g + q] - l) * LOG2E);
+                        float gv = cn * ((v == yt ? 1.0f : 0.0f) - p);
+                        gv = v < V ? gv : 0.0f;
+                        const __bf16 b = (__bf16)gv;   // scalar copy: reading h[q] back right after writing it miscompiles
+                        h[q] = b;
                     }
+                    *reinterpret_cast<bf16x4*>(c.smem + tok * ZPITCH + vloc * 2) = h;
                 }
+        }
+        __syncthreads();
+        constexpr int CH = Cfg::BM / 8;
+        constexpr int ROWS_PER_PASS = Cfg::NT / CH;
+        const int ch = c.tid % CH;
+#pragma unroll 4
+        for (int r = c.tid / CH; r < Cfg::BN; r += ROWS_PER_PASS) {
+            const u32x4 val = *reinterpret_cast<const u32x4*>(c.smem + r * ZPITCH + ch * 16);
+            *reinterpret_cast<u32x4*>(G + blk_offset(c.bn0 + r, c.bm0 + ch * 8, ldg)) = val;
         }
     }
 
     template <class Cfg>
-    static constexpr int lds_bytes() { return 0; }
+    static constexpr int lds_bytes() { return Cfg::BN * (Cfg::BM * 2 + 16); }
 };
 
 }  // namespace mfma

@@ -218,6 +218,41 @@ __global__ __launch_bounds__(256) void grad_logits_kernel(void* ZG, GT_* __restr
     }
 }
 
+// Softmax-gradient pass over a stored bf16-path logits chunk in the blocked layout (blocks of
+// 64 tokens x 256 vocabulary entries, each a contiguous 32 KB run): fp16 logits become bf16
+// gradient entries in place. One workgroup per block; every access is a contiguous 16-byte vector.
+// No transposed copy: the dW GEMM reads the same blocks k-major.
+__global__ __launch_bounds__(256) void grad_logits_blocked_kernel(void* ZG, int32_t V, int64_t ld,
+                                                                  const int32_t* __restrict__ y,
+                                                                  const float* __restrict__ lse,
+                                                                  const float* __restrict__ cvec) {
+    constexpr int BR = 64, BC = 256;
+    const int v_blk = blockIdx.x, n_blk = blockIdx.y;
+    char* base = reinterpret_cast<char*>(ZG) + ((size_t)n_blk * BR * ld + (size_t)v_blk * (BR * BC)) * 2;
+    const int t = threadIdx.x;
+    const int cc = t & 31;               // 16-byte chunk inside a 512-byte block row
+#pragma unroll
+    for (int pass = 0; pass < BR / 8; ++pass) {
+        const int r = (t >> 5) + pass * 8;
+        const int64_t n = (int64_t)n_blk * BR + r;
+        const float l = lse[n], cn = cvec[n];
+        const int yt = y[n];
+        char* p = base + (r * BC + cc * 8) * 2;
+        const f16x8 z = *reinterpret_cast<const f16x8*>(p);
+        bf16x8 g;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int v = v_blk * BC + cc * 8 + q;
+            const float pr = expf((float)z[q] - l);
+            float gv = cn * ((v == yt ? 1.0f : 0.0f) - pr);
+            gv = v < V ? gv : 0.0f;
+            const __bf16 b = (__bf16)gv;   // keep the scalar: reading g[q] back right after writing it miscompiles
+            g[q] = b;
+        }
+        *reinterpret_cast<bf16x8*>(p) = g;
+    }
+}
+
 // ------------------------------------------------------------------------------------
 // One workgroup per packed sequence: token-mean loss, KL sum, clipped count.
 __global__ __launch_bounds__(256) void seq_reduce_kernel(SeqReduceArgs a) {
@@ -347,13 +382,14 @@ void launch_token_loss(const TokenLossArgs& a, ChunkView cv, hipStream_t st) {
 
 void launch_grad_logits(int dtype, void* ZG, void* GT, int32_t V, int32_t Vp, const int32_t* y, const float* lse,
                         const float* c, int32_t n_cp, hipStream_t st) {
-    dim3 grid((unsigned)(Vp / 64), (unsigned)(n_cp / 64));
-    if (dtype == 1)
-        grad_logits_kernel<_Float16, __bf16, f16x8, bf16x8><<<grid, 256, 0, st>>>(
-            ZG, reinterpret_cast<__bf16*>(GT), V, Vp, y, lse, c, n_cp);
-    else
+    if (dtype == 1) {
+        dim3 grid((unsigned)(Vp / 256), (unsigned)(n_cp / 64));
+        grad_logits_blocked_kernel<<<grid, 256, 0, st>>>(ZG, V, Vp, y, lse, c);
+    } else {
+        dim3 grid((unsigned)(Vp / 64), (unsigned)(n_cp / 64));
         grad_logits_kernel<float, float, f32x8, f32x8><<<grid, 256, 0, st>>>(ZG, reinterpret_cast<float*>(GT), V, Vp,
                                                                              y, lse, c, n_cp);
+    }
 }
 
 void launch_seq_reduce(const SeqReduceArgs& a, hipStream_t st) {
