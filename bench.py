@@ -20,6 +20,13 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak
+# L2 <-> fabric bytes per launch from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
+# profiles/bench_qwen3_4b_hbm_traffic.txt (fetch scaled by the factor a plain copy gives). Keyed by
+# (workload, kernel, recompute); an entry is deleted when that kernel changes, until the counters
+# are taken again.
+MEASURED_TRAFFIC_BYTES = {
+    ("qwen3_4b", "logits_gemm", False): 2.0 * 22308039 * 1024 + 9729720 * 1024,
+}
 
 
 def cpu_baseline(rb, pk_host, sel_host, H, W, ids_np, n_sample, seed):
@@ -168,8 +175,9 @@ def main() -> int:
         flop_per_launch = 2.0 * wl.D * wl.V * tokens_per_launch     # 2 D V flop per loss token and GEMM
         avg_ms = ms_tot / launches
         achieved = flop_per_launch / (avg_ms * 1e-3) / 1e12
+        traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, name, bool(args.recompute)))
         roofline = {"bound": "mfma", "kernel": name, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
-                    "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                    "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
                     "avg_launch_ms": avg_ms, "launches_per_step": launches_per_step}
     stage_ms = {k: v[0] / args.steps for k, v in stages.items()}
     mfu = 6.0 * wl.D * wl.V * N / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
