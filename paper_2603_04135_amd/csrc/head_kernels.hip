@@ -89,20 +89,39 @@ __global__ __launch_bounds__(256) void target_logit_kernel(const E* __restrict__
 }
 
 // ------------------------------------------------------------------------------------
-__global__ void combine_logprob_kernel(const float2* __restrict__ part, int32_t n_tiles, const float* __restrict__ zy,
-                                       int64_t n0, int32_t n_c, int32_t n_cp, float* __restrict__ lse_chunk,
-                                       float* __restrict__ logp_out, float* __restrict__ lse_out) {
-    const int n = blockIdx.x * blockDim.x + threadIdx.x;
-    if (n >= n_cp) return;
-    if (n >= n_c) { lse_chunk[n] = 0.0f; return; }
-    float m = -__builtin_inff();
-    for (int t = 0; t < n_tiles; ++t) m = fmaxf(m, part[(size_t)t * n_cp + n].x);
-    float s = 0.0f;
-    for (int t = 0; t < n_tiles; ++t) {
-        const float2 p = part[(size_t)t * n_cp + n];
-        s += p.y * expf(p.x - m);
+// 64 tokens per workgroup, the vocabulary tiles split over 4 wavefronts; each thread folds its
+// tiles into a running (max, sum) pair in one pass, the four pairs of a token meet in LDS.
+__global__ __launch_bounds__(256) void combine_logprob_kernel(const float2* __restrict__ part, int32_t n_tiles,
+                                                              const float* __restrict__ zy, int64_t n0, int32_t n_c,
+                                                              int32_t n_cp, float* __restrict__ lse_chunk,
+                                                              float* __restrict__ logp_out,
+                                                              float* __restrict__ lse_out) {
+    __shared__ float2 red[4][64];
+    const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int n = blockIdx.x * 64 + lane;
+    const float NEG_INF = -__builtin_inff();
+    float m = NEG_INF, s = 0.0f;
+    if (n < n_c) {
+        for (int t = q; t < n_tiles; t += 4) {
+            const float2 p = part[(size_t)t * n_cp + n];
+            if (p.x > m) { s = s * expf(m - p.x) + p.y; m = p.x; }      // exp(-inf) = 0 on the first tile
+            else if (p.x > NEG_INF) s += p.y * expf(p.x - m);
+        }
     }
-    const float lse = m + logf(s);
+    red[q][lane] = make_float2(m, s);
+    __syncthreads();
+    if (q != 0 || n >= n_cp) return;
+    if (n >= n_c) { lse_chunk[n] = 0.0f; return; }
+    float mm = NEG_INF;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) mm = fmaxf(mm, red[i][lane].x);
+    float ss = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float2 r = red[i][lane];
+        ss += (r.x == NEG_INF) ? 0.0f : r.y * expf(r.x - mm);
+    }
+    const float lse = mm + logf(ss);
     lse_chunk[n] = lse;
     logp_out[n0 + n] = zy[n] - lse;
     if (lse_out) lse_out[n0 + n] = lse;
@@ -367,7 +386,7 @@ void launch_target_logit(int dtype, const void* Hc, const void* W, const int32_t
 
 void launch_combine_logprob(const float2* part, int32_t n_tiles, const float* zy, ChunkView cv, float* lse_chunk,
                             float* logp_out, float* lse_out, hipStream_t st) {
-    combine_logprob_kernel<<<(unsigned)ceil_div(cv.n_cp, 64), 64, 0, st>>>(part, n_tiles, zy, cv.n0, cv.n_c, cv.n_cp,
+    combine_logprob_kernel<<<(unsigned)ceil_div(cv.n_cp, 64), 256, 0, st>>>(part, n_tiles, zy, cv.n0, cv.n_c, cv.n_cp,
                                                                             lse_chunk, logp_out, lse_out);
 }
 
