@@ -353,10 +353,75 @@ def token_terms(logp, logp_old, logp_ref, A, clip_lo: float, clip_hi: float, bet
     return ell, g, kl, clipped_away
 
 
+def sequence_terms(logp, logp_old, logp_ref, loss_cu, seq_adv, clip_lo: float, clip_hi: float, beta: float,
+                   ratio_level: str = "token", aggregation: str = "seq_mean"):
+    """Per-sequence loss term (what the rescaling weight multiplies) and its derivative w.r.t. every
+    token log-prob, for the objectives DPPO is plugged into (Sec. 5, robustness across RL algorithms).
+    The paper names the algorithms but prints no formulas for them; the readings taken here:
+
+    ratio_level "token" (GRPO, DAPO): every token has its own ratio, token_terms() above.
+    ratio_level "sequence" (sequence-level likelihood-ratio optimisation): one ratio per sequence,
+        s = (pi(o|q) / pi_old(o|q)) ** (1/|o|) = exp(mean_t (logp_t - logp_old_t)), and every token of the
+        sequence carries  loss_t = -min(s A, clip(s, 1-lo, 1+hi) A) + beta KL_t  (unclipped branch on ties).
+    aggregation "seq_mean" (Eq. 1): term_s = (1/|o|) sum_t loss_t.
+    aggregation "token_sum" (token-level normalisation of the decoupled-clip objective): term_s = sum_t loss_t;
+        the 1 / (tokens of the group) factor belongs to the weight, see token_norm_coef().
+
+    Returns (term[S], dterm_dlogp[N], ell[N], kl[N], clipped_away[N]).
+    """
+    if ratio_level not in ("token", "sequence") or aggregation not in ("seq_mean", "token_sum"):
+        raise ValueError("unknown objective variant")
+    logp = np.asarray(logp, dtype=np.float64)
+    logp_old = np.asarray(logp_old, dtype=np.float64)
+    loss_cu = np.asarray(loss_cu, dtype=np.int64)
+    S = len(loss_cu) - 1
+    N = int(loss_cu[-1])
+    A_tok = np.empty(N)
+    C_tok = np.empty(N)
+    for s in range(S):
+        a, b = int(loss_cu[s]), int(loss_cu[s + 1])
+        A_tok[a:b] = float(seq_adv[s])
+        C_tok[a:b] = b - a
+    ell, g, kl, away = token_terms(logp, logp_old, logp_ref, A_tok, clip_lo, clip_hi, beta)
+    if ratio_level == "sequence":
+        lo, hi = 1.0 - clip_lo, 1.0 + clip_hi
+        rho_hat = np.exp(np.asarray(logp_ref, dtype=np.float64) - logp)
+        for s in range(S):
+            a, b = int(loss_cu[s]), int(loss_cu[s + 1])
+            A = float(seq_adv[s])
+            ratio = np.exp(np.mean(logp[a:b] - logp_old[a:b]))
+            surrogate = min(ratio * A, min(max(ratio, lo), hi) * A)
+            gone = (A > 0 and ratio > hi) or (A < 0 and ratio < lo)
+            ell[a:b] = -surrogate + beta * kl[a:b]
+            away[a:b] = gone
+            # d loss_t' / d logp_t = -(A ratio / |o|) 1[not clipped away] for every pair (t', t) of the
+            # sequence; summed over t' (all |o| tokens carry the term) this is -A ratio per token t
+            g[a:b] = (0.0 if gone else -A * ratio) + beta * (1.0 - rho_hat[a:b])
+    term = np.zeros(S)
+    for s in range(S):
+        a, b = int(loss_cu[s]), int(loss_cu[s + 1])
+        term[s] = ell[a:b].mean() if aggregation == "seq_mean" else ell[a:b].sum()
+    dterm = g / C_tok if aggregation == "seq_mean" else g
+    return term, dterm, ell, kl, away
+
+
+def token_norm_coef(coef, comp_len):
+    """Weights for the token-level normalisation: the group's term is (1 / sum_j |o_j|) sum_i sum_t loss
+    instead of (1/G) sum_i (1/|o_i|) sum_t loss, so coef_i is multiplied by G / sum_j |o_j|, the sum running
+    over ALL G completions of the prompt (their lengths are known before pruning), kept or not.
+    """
+    coef = np.asarray(coef, dtype=np.float64)
+    cl = np.asarray(comp_len, dtype=np.float64).reshape(coef.shape)
+    G = coef.shape[1]
+    return coef * (G / cl.sum(axis=1, keepdims=True))
+
+
 def loss_fwd_bwd(H, W, ids, loss_pos, loss_cu, seq_adv, seq_coef, logp_old, logp_ref,
-                 clip_lo: float = 0.2, clip_hi: float = 0.2, beta: float = 0.04) -> dict:
-    """Loss L = sum_s coef_s * (1/C_s) sum_{n in s} loss_n  (= -J of Eq. 1, reweighted) and
-    its gradients w.r.t. H (rows at loss_pos; all other rows zero) and W.
+                 clip_lo: float = 0.2, clip_hi: float = 0.2, beta: float = 0.04,
+                 ratio_level: str = "token", aggregation: str = "seq_mean") -> dict:
+    """Loss L = sum_s coef_s * term_s, term_s = (1/C_s) sum_{n in s} loss_n  (= -J of Eq. 1, reweighted)
+    or one of the variants of sequence_terms(), and its gradients w.r.t. H (rows at loss_pos; all
+    other rows zero) and W.
 
     Reading: the rescaling weight multiplies the whole per-sequence term (surrogate
     and KL), and |o_i| is the number of completion tokens C_s.
@@ -373,18 +438,14 @@ def loss_fwd_bwd(H, W, ids, loss_pos, loss_cu, seq_adv, seq_coef, logp_old, logp
     lse = m + np.log(np.exp(Z - m[:, None]).sum(axis=1))
     logp = Z[np.arange(N), y] - lse
 
-    A_tok = np.empty(N)
-    w_tok = np.empty(N)
+    seq_loss, dterm, ell, kl, clipped = sequence_terms(logp, logp_old, logp_ref, loss_cu, seq_adv, clip_lo, clip_hi,
+                                                       beta, ratio_level, aggregation)
+    coef_tok = np.empty(N)
     for s in range(S):
-        a, b = int(loss_cu[s]), int(loss_cu[s + 1])
-        A_tok[a:b] = float(seq_adv[s])
-        w_tok[a:b] = float(seq_coef[s]) / (b - a)
-    ell, g, kl, clipped = token_terms(logp, logp_old, logp_ref, A_tok, clip_lo, clip_hi, beta)
-    seq_loss = np.array([ell[int(loss_cu[s]):int(loss_cu[s + 1])].mean() for s in range(S)]) \
-        if S else np.zeros(0)
+        coef_tok[int(loss_cu[s]):int(loss_cu[s + 1])] = float(seq_coef[s])
     loss = float(np.sum(np.asarray(seq_coef, dtype=np.float64) * seq_loss))
 
-    c = w_tok * g                                  # dL/dlogp[n]
+    c = coef_tok * dterm                           # dL/dlogp[n]
     dZ = -np.exp(Z - lse[:, None]) * c[:, None]    # -c_n p[n,v]
     dZ[np.arange(N), y] += c                       # + c_n 1[v = y_n]
     dH = np.zeros_like(H)

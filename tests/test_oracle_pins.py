@@ -652,3 +652,111 @@ def test_expected_loss_and_gradients_are_unbiased_over_all_masks():
     assert np.allclose(EdW, dW0, rtol=1e-9, atol=1e-13)
     for j in range(Q * G):
         assert np.allclose(EdH[j], dH0[j], rtol=1e-9, atol=1e-13)
+
+
+# ------------------------------------------- objective variants (sequence ratio, token normalisation)
+VARIANTS = [("token", "seq_mean"), ("token", "token_sum"), ("sequence", "seq_mean"), ("sequence", "token_sum")]
+
+
+@pytest.mark.parametrize("ratio_level,aggregation", VARIANTS)
+def test_variant_loss_and_grads_match_autograd(ratio_level, aggregation):
+    import torch
+    p, H, W, ids, old, ref, adv, coef = _loss_case(5, clip_noise=0.4)
+    lo, hi, beta = 0.2, 0.28, 0.04
+    out = O.loss_fwd_bwd(H, W, ids, p["loss_pos"], p["loss_cu"], adv, coef, old, ref, lo, hi, beta,
+                         ratio_level=ratio_level, aggregation=aggregation)
+    assert 0.0 < out["clip_frac"] < 1.0
+    Ht = torch.tensor(H, requires_grad=True)
+    Wt = torch.tensor(W, requires_grad=True)
+    lp = torch.tensor(p["loss_pos"]).long()
+    y = torch.tensor(ids[p["loss_pos"] + 1]).long()
+    logp = torch.log_softmax(Ht[lp] @ Wt.T, dim=-1).gather(1, y[:, None])[:, 0]
+    total = torch.zeros((), dtype=torch.float64)
+    for s in range(4):
+        a, b = int(p["loss_cu"][s]), int(p["loss_cu"][s + 1])
+        d = logp[a:b] - torch.tensor(old[a:b])
+        rho = torch.exp(d.mean()).expand(b - a) if ratio_level == "sequence" else torch.exp(d)
+        sur = torch.minimum(rho * adv[s], torch.clamp(rho, 1 - lo, 1 + hi) * adv[s])
+        rh = torch.exp(torch.tensor(ref[a:b]) - logp[a:b])
+        per_tok = -sur + beta * (rh - torch.log(rh) - 1)
+        total = total + coef[s] * (per_tok.mean() if aggregation == "seq_mean" else per_tok.sum())
+    total.backward()
+    assert math.isclose(out["loss"], float(total.detach()), rel_tol=1e-12)
+    assert np.allclose(out["dH"], Ht.grad.numpy(), rtol=1e-10, atol=1e-14)
+    assert np.allclose(out["dW"], Wt.grad.numpy(), rtol=1e-10, atol=1e-14)
+
+
+def test_sequence_ratio_is_the_geometric_mean_of_token_ratios():
+    from fractions import Fraction
+    # log-ratios that are exact binary fractions: exp(mean) = (prod of token ratios)^(1/C)
+    cu = np.array([0, 3, 4, 8])
+    d = np.array([0.5, -0.25, 0.125, 0.75, -0.5, 0.25, 0.0, -0.125])
+    logp = -np.arange(1, 9) * 0.5
+    old = logp - d
+    adv = np.array([1.0, -2.0, 0.5])
+    term, dterm, ell, kl, away = O.sequence_terms(logp, old, logp, cu, adv, 0.3, 0.3, 0.0, "sequence", "seq_mean")
+    for s in range(3):
+        a, b = cu[s], cu[s + 1]
+        geo = math.prod(math.exp(x) for x in d[a:b]) ** (1.0 / (b - a))
+        want = -min(geo * adv[s], min(max(geo, 0.7), 1.3) * adv[s])
+        assert math.isclose(term[s], want, rel_tol=1e-12)
+        assert np.all(ell[a:b] == ell[a])           # every token of a sequence carries the same term
+    # sequence 1: ratio exp(0.75) = 2.117 > 1.3 with A < 0: not clipped away (the min keeps the unclipped branch)
+    assert not away[3] and dterm[3] == -adv[1] * math.exp(0.75)
+    # sequence 0: ratio exp(0.125) inside the interval; sequence 2: exp(-0.09375), inside too
+    assert not away[:3].any() and not away[4:].any()
+    # a sequence whose ratio leaves the interval on the penalised side gets no gradient
+    term, dterm, _, _, away = O.sequence_terms(logp, old, logp, cu, -adv, 0.3, 0.3, 0.0, "sequence", "seq_mean")
+    assert away[3] and dterm[3] == 0.0 and math.isclose(term[1], -(1.3 * 2.0), rel_tol=1e-12)
+
+
+def test_variants_reduce_to_eq1_in_their_special_cases():
+    rng = np.random.default_rng(8)
+    # (a) one-token completions: a sequence ratio is its token ratio
+    cu = np.arange(0, 8)
+    logp, old, ref = -rng.random(7), -rng.random(7), -rng.random(7)
+    adv = rng.normal(size=7)
+    base = O.sequence_terms(logp, old, ref, cu, adv, 0.2, 0.2, 0.04, "token", "seq_mean")
+    for rl, ag in VARIANTS[1:]:
+        other = O.sequence_terms(logp, old, ref, cu, adv, 0.2, 0.2, 0.04, rl, ag)
+        for x, y in zip(base, other):
+            assert np.allclose(x, y, rtol=1e-14, atol=0)
+    # (b) equal lengths C: the token sum is C times the token mean, for both ratio levels
+    cu = np.arange(0, 13, 4)
+    logp, old, ref = -rng.random(12), -rng.random(12), -rng.random(12)
+    adv = rng.normal(size=3)
+    for rl in ("token", "sequence"):
+        m = O.sequence_terms(logp, old, ref, cu, adv, 0.2, 0.2, 0.04, rl, "seq_mean")
+        t = O.sequence_terms(logp, old, ref, cu, adv, 0.2, 0.2, 0.04, rl, "token_sum")
+        assert np.allclose(t[0], 4 * m[0], rtol=1e-14) and np.allclose(t[1], 4 * m[1], rtol=1e-14)
+    # (c) coincident policies: ratio 1 at either level, term = -A (mean) or -A |o| (sum)
+    cu = np.array([0, 2, 7])
+    lp = -rng.random(7)
+    for rl in ("token", "sequence"):
+        term, dterm, _, kl, away = O.sequence_terms(lp, lp, lp, cu, np.array([0.5, -1.5]), 0.2, 0.2, 0.04, rl, "token_sum")
+        assert np.allclose(term, [-0.5 * 2, 1.5 * 5], rtol=1e-14) and not away.any() and np.all(kl == 0)
+        assert np.allclose(dterm, np.repeat([-0.5, 1.5], [2, 5]), rtol=1e-14)
+    with pytest.raises(ValueError):
+        O.sequence_terms(lp, lp, lp, cu, np.zeros(2), 0.2, 0.2, 0.0, "word", "seq_mean")
+
+
+def test_token_norm_coef_makes_the_token_level_objective_unbiased():
+    # unpruned: sum_i coef'_i sum_t l = (1/Q) sum_q (1 / tokens of the group) sum_{i,t} l
+    rng = np.random.default_rng(31)
+    Q, G = 2, 3
+    cl = rng.integers(1, 6, size=(Q, G))
+    tok_loss = [[rng.normal(size=cl[q, i]) for i in range(G)] for q in range(Q)]
+    direct = np.mean([sum(x.sum() for x in tok_loss[q]) / cl[q].sum() for q in range(Q)])
+    rewards = np.array([[1, 1, 1], [0, 1, 0]], dtype=np.float32)
+    hist = np.array([0.3, 0.1], dtype=np.float32)
+    s0 = O.select(rewards, None, None, None, 0.0, 0.0)
+    c0 = O.token_norm_coef(s0["coef"], cl)
+    assert math.isclose(sum(c0[q, i] * tok_loss[q][i].sum() for q in range(Q) for i in range(G)), direct, rel_tol=1e-12)
+    # pruned: the expectation over all masks is the same number (lengths of pruned completions still count)
+    r_q, r_o = 0.5, 0.375
+    E = 0.0
+    for prob, up, uc in _enumerate_masks(rewards, hist, r_q, r_o):
+        s = O.select(rewards, hist, up, uc, r_q, r_o)
+        c = O.token_norm_coef(s["coef"], cl)
+        E += prob * sum(c[q, i] * tok_loss[q][i].sum() for q in range(Q) for i in range(G))
+    assert math.isclose(E, direct, rel_tol=1e-10)
