@@ -189,12 +189,27 @@ int dppo_token_logprob(const dppo_head_shape* shape,
  * clipped away, N, 0}. loss is one float on the device.
  * recompute_logits = 0 keeps one chunk of logits in the workspace as fp16 (needs
  * |z| < 65504); 1 runs the vocabulary GEMM a second time in the backward instead.
+ *
+ * Variants for the other objectives the method is plugged into (Sec. 5, robustness across RL
+ * algorithms; the paper names them without formulas, these are this library's readings):
+ *   ratio_level = DPPO_RATIO_SEQUENCE: one ratio per sequence, exp(mean_n (logp - logp_old)), takes
+ *     the place of rho in every token of the sequence (clip and min as above; KL stays per token).
+ *     It needs the log-probs of a whole sequence before any of its gradients, so the vocabulary
+ *     GEMM runs one extra forward pass over all tokens first.
+ *   aggregation = DPPO_AGG_TOKEN_SUM: the per-sequence term is sum_n l_n instead of the mean; with
+ *     weights from dppo_token_norm_coef this is the token-level normalisation of the decoupled-clip
+ *     objective (clip_lo != clip_hi is the decoupled clip itself). seq_loss then holds the sums.
  */
+enum { DPPO_RATIO_TOKEN = 0, DPPO_RATIO_SEQUENCE = 1 };
+enum { DPPO_AGG_SEQ_MEAN = 0, DPPO_AGG_TOKEN_SUM = 1 };
+
 typedef struct {
     float clip_lo, clip_hi;
     float beta;
     int32_t accumulate_dW;
     int32_t recompute_logits;
+    int32_t ratio_level;   /* DPPO_RATIO_TOKEN (Eq. 1) or DPPO_RATIO_SEQUENCE */
+    int32_t aggregation;   /* DPPO_AGG_SEQ_MEAN (Eq. 1) or DPPO_AGG_TOKEN_SUM */
 } dppo_loss_params;
 
 int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* p, int32_t S,
@@ -206,6 +221,12 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* p, i
                       float* stats /* or NULL */,
                       void* dH, float* dW,
                       void* ws, size_t ws_bytes, void* stream);
+
+/* coef_out[q*G+i] = coef[q*G+i] * G / sum_j comp_len[q*G+j]: weights for DPPO_AGG_TOKEN_SUM. The sum runs
+ * over all G completions of the prompt, pruned ones included (their lengths are known before
+ * pruning). Device arrays; coef_out may alias coef. A group whose lengths sum to <= 0 gets 0. */
+int dppo_token_norm_coef(int32_t Q, int32_t G, const int32_t* comp_len, const float* coef, float* coef_out,
+                         void* stream);
 
 /* --------------------------------------------------------------------------------
  * Optional stage timing, for benchmarks. While enabled, dppo_token_logprob and

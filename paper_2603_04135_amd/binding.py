@@ -17,7 +17,7 @@ import torch
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdppo_hip.so")
 _lib = None
 
-EXPORTS = ["dppo_status_str", "dppo_last_error", "dppo_select", "dppo_pack", "dppo_gather_f32",
+EXPORTS = ["dppo_status_str", "dppo_last_error", "dppo_select", "dppo_pack", "dppo_gather_f32", "dppo_token_norm_coef",
            "dppo_workspace_bytes", "dppo_workspace_min_bytes", "dppo_token_logprob", "dppo_loss_fwd_bwd",
            "dppo_timing_enable", "dppo_timing_read", "dppo_history_update"]
 STAGES = ["logits_gemm", "grad_logits", "dh_gemm", "dw_gemm"]
@@ -48,7 +48,12 @@ class HeadShape(ctypes.Structure):
 
 class LossParams(ctypes.Structure):
     _fields_ = [("clip_lo", c_float), ("clip_hi", c_float), ("beta", c_float),
-                ("accumulate_dW", c_int32), ("recompute_logits", c_int32)]
+                ("accumulate_dW", c_int32), ("recompute_logits", c_int32),
+                ("ratio_level", c_int32), ("aggregation", c_int32)]
+
+
+RATIO_LEVELS = {"token": 0, "sequence": 1}
+AGGREGATIONS = {"seq_mean": 0, "token_sum": 1}
 
 
 def library_path() -> str:
@@ -72,6 +77,8 @@ def load():
     lib.dppo_select.argtypes = [POINTER(SelectParams)] + [c_void_p] * 13
     lib.dppo_pack.restype = c_int
     lib.dppo_pack.argtypes = [POINTER(PackParams)] + [c_void_p] * 8 + [c_int64, c_void_p, c_void_p]
+    lib.dppo_token_norm_coef.restype = c_int
+    lib.dppo_token_norm_coef.argtypes = [c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.dppo_gather_f32.restype = c_int
     lib.dppo_gather_f32.argtypes = [c_int64, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.dppo_workspace_bytes.restype = c_size_t
@@ -204,6 +211,19 @@ def dppo_pack(prompt_len, comp_len, keep, capacity: int, n_win: int, loss_pos_ca
                 density=(T / (n_rows * cap)) if n_rows else 0.0)
 
 
+def dppo_token_norm_coef(coef: torch.Tensor, comp_len) -> torch.Tensor:
+    """coef [Q,G] float32, comp_len [Q,G] int32 -> coef * G / (completion tokens of the group)."""
+    lib = load()
+    device = coef.device
+    Q, G = coef.shape
+    coef = _as(coef, torch.float32, device)
+    comp_len = _as(comp_len, torch.int32, device)
+    out = torch.empty_like(coef)
+    _check(lib.dppo_token_norm_coef(Q, G, _ptr(comp_len), _ptr(coef), _ptr(out), _stream(device)),
+           "dppo_token_norm_coef")
+    return out
+
+
 def dppo_gather_f32(idx: torch.Tensor, src: torch.Tensor) -> torch.Tensor:
     lib = load()
     device = src.device
@@ -256,7 +276,8 @@ def dppo_loss_fwd_bwd(H, W, ids, loss_pos, loss_cu, seq_adv, seq_coef, logp_old,
                       clip_lo: float = 0.2, clip_hi: float = 0.2, beta: float = 0.04,
                       dW: Optional[torch.Tensor] = None, accumulate_dW: bool = False,
                       recompute_logits: bool = False, ws: Optional[torch.Tensor] = None,
-                      dH: Optional[torch.Tensor] = None, out: Optional[dict] = None) -> dict:
+                      dH: Optional[torch.Tensor] = None, out: Optional[dict] = None,
+                      ratio_level: str = "token", aggregation: str = "seq_mean") -> dict:
     """Returns dict(loss[1], logp[N], seq_loss[S], stats[4], dH[T,D], dW[V,D]) of device tensors."""
     lib = load()
     device = H.device
@@ -275,7 +296,8 @@ def dppo_loss_fwd_bwd(H, W, ids, loss_pos, loss_cu, seq_adv, seq_coef, logp_old,
         if accumulate_dW:
             raise ValueError("accumulate_dW needs the dW buffer to accumulate into")
         dW = torch.empty(W.shape, **f32)
-    p = LossParams(clip_lo, clip_hi, beta, 1 if accumulate_dW else 0, 1 if recompute_logits else 0)
+    p = LossParams(clip_lo, clip_hi, beta, 1 if accumulate_dW else 0, 1 if recompute_logits else 0,
+                   RATIO_LEVELS[ratio_level], AGGREGATIONS[aggregation])
     st = lib.dppo_loss_fwd_bwd(ctypes.byref(shape), ctypes.byref(p), S, _ptr(H), _ptr(W), _ptr(ids), _ptr(loss_pos),
                                _ptr(loss_cu), _ptr(seq_adv), _ptr(seq_coef), _ptr(logp_old), _ptr(logp_ref),
                                _ptr(out["loss"]), _ptr(out["logp"]), _ptr(out["seq_loss"]), _ptr(out["stats"]),

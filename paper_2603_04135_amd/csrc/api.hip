@@ -72,7 +72,7 @@ struct WsPlan {
     size_t es, zs;                 // element sizes of H/W and of the stored logits / gradient entries
     size_t fixed_bytes, row_bytes; // bytes independent of / proportional to the chunk size
     // region offsets
-    size_t o_wt, o_logp, o_ell, o_kl, o_clip, o_seq, o_hc, o_hct, o_part, o_zg, o_gt, o_y, o_zy, o_lse, o_c;
+    size_t o_wt, o_logp, o_ell, o_kl, o_clip, o_seq, o_sratio, o_hc, o_hct, o_part, o_zg, o_gt, o_y, o_zy, o_lse, o_c;
     size_t total;
 };
 
@@ -95,6 +95,7 @@ void layout(const dppo_head_shape& s, bool bwd, int32_t n_cp, WsPlan& p) {
     p.o_kl = take(bwd ? N * 4 : 0);
     p.o_clip = take(bwd ? N * 4 : 0);
     p.o_seq = take(bwd ? 3 * N * 4 : 0);
+    p.o_sratio = take(bwd ? N * 4 : 0);
     p.fixed_bytes = off;
     p.o_hc = take((size_t)n_cp * s.D * p.es);
     p.o_hct = take(bwd ? (size_t)n_cp * s.D * p.es : 0);
@@ -258,6 +259,14 @@ int dppo_pack(const dppo_pack_params* p, const int32_t* prompt_len, const int32_
     return check_launch("dppo_pack");
 }
 
+int dppo_token_norm_coef(int32_t Q, int32_t G, const int32_t* comp_len, const float* coef, float* coef_out,
+                         void* stream) {
+    if (Q <= 0 || G <= 0) return fail(DPPO_ERR_SHAPE, "Q and G must be positive (Q=%d G=%d)", Q, G);
+    if (!comp_len || !coef || !coef_out) return fail(DPPO_ERR_INVALID_ARG, "a required array pointer is NULL");
+    launch_token_norm_coef(Q, G, comp_len, coef, coef_out, (hipStream_t)stream);
+    return check_launch("dppo_token_norm_coef");
+}
+
 int dppo_gather_f32(int64_t n, const int32_t* idx, const float* src, float* dst, void* stream) {
     if (n < 0) return fail(DPPO_ERR_SHAPE, "n is negative");
     if (n == 0) return DPPO_OK;
@@ -341,6 +350,9 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
     if (!(lp->clip_lo >= 0.0f && lp->clip_lo < 1.0f) || !(lp->clip_hi >= 0.0f))
         return fail(DPPO_ERR_INVALID_ARG, "need 0 <= clip_lo < 1 and clip_hi >= 0");
     if (!(lp->beta >= 0.0f)) return fail(DPPO_ERR_INVALID_ARG, "beta must be >= 0");
+    if ((lp->ratio_level != DPPO_RATIO_TOKEN && lp->ratio_level != DPPO_RATIO_SEQUENCE) ||
+        (lp->aggregation != DPPO_AGG_SEQ_MEAN && lp->aggregation != DPPO_AGG_TOKEN_SUM))
+        return fail(DPPO_ERR_INVALID_ARG, "unknown ratio_level %d or aggregation %d", lp->ratio_level, lp->aggregation);
     if (S < 0 || (s.N > 0 && S < 1) || (int64_t)S > s.N) return fail(DPPO_ERR_SHAPE, "need 1 <= S <= N when N > 0 (S=%d N=%lld)", S, (long long)s.N);
     if (!loss || !dH || !dW || !W) return fail(DPPO_ERR_INVALID_ARG, "loss, dH, dW and W must not be NULL");
     if (s.N > 0 && (!H || !ids || !loss_cu || !seq_adv || !seq_coef || !logp_old || !logp_ref))
@@ -367,6 +379,20 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
     if (!lp->accumulate_dW && s.N == 0) launch_fill_zero(dW, (size_t)s.V * s.D * 4, st);
     if (s.N > 0) launch_transpose_w(s.dtype, W, s.V, s.D, p.Vp, w + p.o_wt, st);
 
+    float* seq_ratio = reinterpret_cast<float*>(w + p.o_sratio);
+    if (lp->ratio_level == DPPO_RATIO_SEQUENCE && s.N > 0) {
+        // a sequence's ratio needs all its log-probs, and a sequence may straddle chunks: one
+        // forward-only pass over every chunk first
+        for (int64_t n0 = 0; n0 < s.N; n0 += p.n_cp) {
+            ChunkView cv;
+            cv.n0 = n0;
+            cv.n_c = (int32_t)((s.N - n0) < p.n_cp ? (s.N - n0) : p.n_cp);
+            cv.n_cp = round_up32(cv.n_c, CHUNK_ALIGN);
+            if (int rc = chunk_forward(s, p, w, H, W, ids, loss_pos, cv, false, false, logp_all, nullptr, st)) return rc;
+        }
+        launch_seq_ratio(loss_cu, S, logp_all, logp_old, seq_ratio, st);
+    }
+
     bool first = true;
     for (int64_t n0 = 0; n0 < s.N; n0 += p.n_cp) {
         ChunkView cv;
@@ -380,6 +406,7 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
         ta.loss_cu = loss_cu; ta.S = S; ta.seq_adv = seq_adv; ta.seq_coef = seq_coef;
         ta.logp_old = logp_old; ta.logp_ref = logp_ref; ta.logp = logp_all;
         ta.lo = (float)(1.0 - (double)lp->clip_lo); ta.hi = (float)(1.0 + (double)lp->clip_hi); ta.beta = lp->beta;
+        ta.ratio_level = lp->ratio_level; ta.aggregation = lp->aggregation; ta.seq_ratio = seq_ratio;
         ta.c_chunk = reinterpret_cast<float*>(w + p.o_c);
         ta.ell = ell; ta.kl = kl; ta.clipped = clipf;
         launch_token_loss(ta, cv, st);
@@ -428,6 +455,7 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
 
     SeqReduceArgs ra;
     ra.loss_cu = loss_cu; ra.S = s.N > 0 ? S : 0; ra.N = s.N; ra.seq_coef = seq_coef;
+    ra.aggregation = lp->aggregation;
     ra.ell = ell; ra.kl = kl; ra.clipped = clipf;
     ra.seq_mean = seq_tmp; ra.seq_kl = seq_tmp + s.N; ra.seq_clip = seq_tmp + 2 * s.N;
     ra.seq_loss_out = seq_loss; ra.loss_out = loss; ra.stats_out = stats;

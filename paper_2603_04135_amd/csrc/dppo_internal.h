@@ -64,10 +64,17 @@ struct TokenLossArgs {
     const float* logp_old; const float* logp_ref;
     const float* logp;      // [N] current-policy log-probs (written by the combine step)
     float lo, hi, beta;     // ratio bounds 1-clip_lo, 1+clip_hi and KL weight
+    int32_t ratio_level, aggregation;
+    const float* seq_ratio; // [S] sequence-level ratio (ratio_level 1), else unused
     float* c_chunk;         // [n_cp] dL/dlogp of the chunk's tokens (0 beyond n_c)
     float* ell; float* kl; float* clipped;   // [N] per-token loss, KL, clipped-away flag
 };
 void launch_token_loss(const TokenLossArgs& a, ChunkView cv, hipStream_t st);
+// seq_ratio[s] = exp(mean over the sequence's tokens of logp - logp_old).
+void launch_seq_ratio(const int32_t* loss_cu, int32_t S, const float* logp, const float* logp_old,
+                      float* seq_ratio, hipStream_t st);
+void launch_token_norm_coef(int32_t Q, int32_t G, const int32_t* comp_len, const float* coef, float* coef_out,
+                            hipStream_t st);
 
 // In place over the chunk's stored logits: G[n,v] = c[n] (1[v==y[n]] - exp(z - lse[n])) for
 // v < V, 0 for V <= v < Vp.
@@ -80,6 +87,7 @@ void launch_grad_logits(int dtype, void* ZG, void* GT, int32_t V, int32_t Vp, co
 struct SeqReduceArgs {
     const int32_t* loss_cu; int32_t S; int64_t N;
     const float* seq_coef;
+    int32_t aggregation;    // 0: per-sequence mean of ell, 1: sum
     const float* ell; const float* kl; const float* clipped;
     float* seq_mean; float* seq_kl; float* seq_clip;   // [S] scratch
     float* seq_loss_out;                                // [S] or NULL

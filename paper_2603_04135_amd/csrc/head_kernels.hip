@@ -163,7 +163,8 @@ __global__ __launch_bounds__(256) void row_stats_kernel(const float* __restrict_
 }
 
 // ------------------------------------------------------------------------------------
-// Per-token terms of Eq. 1 and d(loss)/d(logp), weighted by seq_coef / C_s.
+// Per-token terms of Eq. 1 and d(loss)/d(logp), weighted by seq_coef / C_s (token-sum aggregation:
+// by seq_coef). With a sequence-level ratio every token of a sequence uses the same rho.
 __global__ void token_loss_kernel(TokenLossArgs a, int64_t n0, int32_t n_c, int32_t n_cp) {
     const int n = blockIdx.x * blockDim.x + threadIdx.x;
     if (n >= n_cp) return;
@@ -176,11 +177,12 @@ __global__ void token_loss_kernel(TokenLossArgs a, int64_t n0, int32_t n_c, int3
     }
     const int s = lo;
     const float A = a.seq_adv[s];
-    const float w = a.seq_coef[s] / (float)(a.loss_cu[s + 1] - a.loss_cu[s]);
+    const float w = a.aggregation == DPPO_AGG_TOKEN_SUM ? a.seq_coef[s]
+                                                       : a.seq_coef[s] / (float)(a.loss_cu[s + 1] - a.loss_cu[s]);
     const float lp = a.logp[gi];
     const float d_old = lp - a.logp_old[gi];
     const float d_ref = a.logp_ref[gi] - lp;
-    const float rho = expf(d_old);
+    const float rho = a.ratio_level == DPPO_RATIO_SEQUENCE ? a.seq_ratio[s] : expf(d_old);
     const float unclipped = rho * A;
     const float clipped = fminf(fmaxf(rho, a.lo), a.hi) * A;
     const float sur = fminf(unclipped, clipped);
@@ -272,8 +274,40 @@ __global__ __launch_bounds__(256) void grad_logits_blocked_kernel(void* ZG, int3
     }
 }
 
+// One workgroup per packed sequence: exp of the mean log-ratio over its tokens.
+__global__ __launch_bounds__(256) void seq_ratio_kernel(const int32_t* __restrict__ loss_cu, int32_t S,
+                                                        const float* __restrict__ logp,
+                                                        const float* __restrict__ logp_old,
+                                                        float* __restrict__ seq_ratio) {
+    __shared__ float r0[256];
+    for (int s = blockIdx.x; s < S; s += gridDim.x) {
+        const int b = loss_cu[s], e = loss_cu[s + 1];
+        float x = 0.0f;
+        for (int i = b + threadIdx.x; i < e; i += 256) x += logp[i] - logp_old[i];
+        r0[threadIdx.x] = x;
+        __syncthreads();
+        for (int st = 128; st > 0; st >>= 1) {
+            if (threadIdx.x < st) r0[threadIdx.x] += r0[threadIdx.x + st];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) seq_ratio[s] = expf(r0[0] / (float)(e - b));
+        __syncthreads();
+    }
+}
+
+// One thread per prompt group: coef * G / (completion tokens of the whole group).
+__global__ void token_norm_coef_kernel(int32_t Q, int32_t G, const int32_t* __restrict__ comp_len,
+                                       const float* coef, float* coef_out) {
+    const int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= Q) return;
+    int64_t tot = 0;
+    for (int i = 0; i < G; ++i) tot += comp_len[(size_t)q * G + i];
+    const float f = tot > 0 ? (float)((double)G / (double)tot) : 0.0f;
+    for (int i = 0; i < G; ++i) coef_out[(size_t)q * G + i] = coef[(size_t)q * G + i] * f;
+}
+
 // ------------------------------------------------------------------------------------
-// One workgroup per packed sequence: token-mean loss, KL sum, clipped count.
+// One workgroup per packed sequence: token-mean (or token-sum) loss, KL sum, clipped count.
 __global__ __launch_bounds__(256) void seq_reduce_kernel(SeqReduceArgs a) {
     __shared__ float r0[256], r1[256], r2[256];
     for (int s = blockIdx.x; s < a.S; s += gridDim.x) {
@@ -291,7 +325,7 @@ __global__ __launch_bounds__(256) void seq_reduce_kernel(SeqReduceArgs a) {
             __syncthreads();
         }
         if (threadIdx.x == 0) {
-            const float mean = r0[0] / (float)(e - b);
+            const float mean = a.aggregation == DPPO_AGG_TOKEN_SUM ? r0[0] : r0[0] / (float)(e - b);
             a.seq_mean[s] = mean;
             a.seq_kl[s] = r1[0];
             a.seq_clip[s] = r2[0];
@@ -397,6 +431,18 @@ void launch_row_stats_f32(const float* Z, int64_t ldz, int32_t V, const int32_t*
 
 void launch_token_loss(const TokenLossArgs& a, ChunkView cv, hipStream_t st) {
     token_loss_kernel<<<(unsigned)ceil_div(cv.n_cp, 256), 256, 0, st>>>(a, cv.n0, cv.n_c, cv.n_cp);
+}
+
+void launch_seq_ratio(const int32_t* loss_cu, int32_t S, const float* logp, const float* logp_old,
+                      float* seq_ratio, hipStream_t st) {
+    if (S <= 0) return;
+    const unsigned blocks = S < 4096 ? (unsigned)S : 4096u;
+    seq_ratio_kernel<<<blocks, 256, 0, st>>>(loss_cu, S, logp, logp_old, seq_ratio);
+}
+
+void launch_token_norm_coef(int32_t Q, int32_t G, const int32_t* comp_len, const float* coef, float* coef_out,
+                            hipStream_t st) {
+    token_norm_coef_kernel<<<(unsigned)ceil_div(Q, 64), 64, 0, st>>>(Q, G, comp_len, coef, coef_out);
 }
 
 void launch_grad_logits(int dtype, void* ZG, void* GT, int32_t V, int32_t Vp, const int32_t* y, const float* lse,

@@ -88,7 +88,8 @@ class HeadCase:
         return O.loss_fwd_bwd(H64, W64, self.ids_np, self.pk["loss_pos"], self.pk["loss_cu"],
                               self.seq_adv_np, self.seq_coef_np, self.logp_old_np, self.logp_ref_np,
                               kw.get("clip_lo", wl.clip_eps), kw.get("clip_hi", wl.clip_eps),
-                              kw.get("beta", wl.kl_beta))
+                              kw.get("beta", wl.kl_beta), ratio_level=kw.get("ratio_level", "token"),
+                              aggregation=kw.get("aggregation", "seq_mean"))
 
 
 def rel_fro(a: np.ndarray, b: np.ndarray) -> float:

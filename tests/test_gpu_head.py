@@ -123,6 +123,54 @@ def test_clipping_zero_advantage_and_single_token_sequences(lib):
     _run_case(lib, case32, TOL["f32"], clip_lo=0.2, clip_hi=0.28, beta=0.1)
 
 
+VARIANTS = [("token", "token_sum"), ("sequence", "seq_mean"), ("sequence", "token_sum")]
+
+
+@pytest.mark.parametrize("ratio_level,aggregation", VARIANTS)
+def test_objective_variants(lib, ratio_level, aggregation):
+    """Sequence-level ratio and token-sum aggregation (the objectives the method is plugged into), with a
+    decoupled clip tight enough that whole sequences are clipped away at the sequence level."""
+    rb = WL.make_rollout("small")
+    wl = rb.wl
+    sel, pk = oracle_select_pack(rb)
+    # token-normalised weights for the token sum: coef * G / (completion tokens of the group)
+    if aggregation == "token_sum":
+        want = O.token_norm_coef(sel["coef"], rb.comp_len)
+        got = lib.dppo_token_norm_coef(torch.as_tensor(sel["coef"].astype(np.float32), device=DEV), rb.comp_len)
+        assert np.allclose(got.cpu().numpy(), want, rtol=2e-6, atol=0)
+        sel = dict(sel, coef=want)
+    # advantages of both signs on every sequence (the workload's own are mostly zero on a short prefix)
+    sel = dict(sel, adv=np.random.default_rng(12).normal(size=sel["adv"].shape).astype(np.float32))
+    pk = truncate_pack(pk, 6000)
+    case = HeadCase(wl, pk, sel, rb.seed, DEV, logp_noise=0.3)
+    clip = dict(clip_lo=0.2, clip_hi=0.28)
+    if ratio_level == "sequence":
+        # sequence ratios sit much closer to 1 than token ratios: clip at their median distance from 1
+        base, _ = case.oracle_logprob()
+        case.set_behaviour_logps(base)
+        cu = case.pk["loss_cu"]
+        dist = [abs(np.expm1(np.mean(base[cu[i]:cu[i + 1]] - case.logp_old_np[cu[i]:cu[i + 1]]))) for i in range(len(cu) - 1)]
+        clip = dict(clip_lo=float(np.median(dist)), clip_hi=float(np.median(dist)) * 1.5)
+    out, ref = _run_case(lib, case, TOL["bf16"], beta=0.04, ratio_level=ratio_level, aggregation=aggregation, **clip)
+    assert 0.0 < ref["clip_frac"] < 1.0
+    # the workspace-limited (several chunks) and recompute paths agree with the default one
+    T, N, D, V = case.pk["T"], case.pk["N"], wl.D, wl.V
+    ws_min, ws_full = lib.dppo_workspace_min_bytes(T, N, D, V, 1, True), lib.dppo_workspace_bytes(T, N, D, V, 1, True)
+    args = (case.H, case.W, case.ids, case.loss_pos, case.loss_cu, case.seq_adv, case.seq_coef, case.logp_old,
+            case.logp_ref)
+    kw = dict(beta=0.04, ratio_level=ratio_level, aggregation=aggregation, **clip)
+    small = lib.dppo_loss_fwd_bwd(*args, ws=lib.alloc_workspace((ws_min + ws_full) // 2, DEV), **kw)
+    assert torch.equal(small["dH"], out["dH"]) and torch.equal(small["seq_loss"], out["seq_loss"])
+    rec = lib.dppo_loss_fwd_bwd(*args, recompute_logits=True, **kw)
+    assert rel_fro(to_np64(rec["dW"]), ref["dW"]) <= 1e-2 and float(rec["loss"]) == float(out["loss"])
+
+
+def test_objective_variants_fp32(lib):
+    case = _case("tiny", None)
+    for ratio_level, aggregation in VARIANTS:
+        _run_case(lib, case, TOL["f32"], clip_lo=0.002, clip_hi=0.003, ratio_level=ratio_level, aggregation=aggregation)
+
+
 def test_coincident_policies(lib):
     case = _case("tiny", None, dtype="bf16")
     logp, _ = lib.dppo_token_logprob(case.H, case.W, case.ids, case.loss_pos)

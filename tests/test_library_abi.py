@@ -66,6 +66,9 @@ def test_host_side_validation_launches_nothing(lib):
     lp = LossParams(0.2, 0.2, 0.04, 0, 0)
     assert lib.dppo_loss_fwd_bwd(ctypes.byref(hs), ctypes.byref(lp), 3, *([one] * 15), one, 1024, None) == 4
     assert lib.dppo_token_logprob(ctypes.byref(hs), *([one] * 6), None, 1 << 20, None) == 4
+    lp = LossParams(0.2, 0.2, 0.04, 0, 0, 2, 0)          # unknown ratio level
+    assert lib.dppo_loss_fwd_bwd(ctypes.byref(hs), ctypes.byref(lp), 3, *([one] * 15), one, 1 << 30, None) == 1
+    assert lib.dppo_token_norm_coef(0, 4, one, one, one, None) == 2
 
 
 def test_workspace_sizes(lib):
