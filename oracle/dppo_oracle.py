@@ -300,6 +300,54 @@ def pack(prompt_len, comp_len, keep, capacity, n_win: int, policy: str = "first_
 
 
 # ----------------------------------------------------------------------------
+# Variance of the rescaled single-sample estimator (App. D)
+# ----------------------------------------------------------------------------
+def variance_terms(g, P_q, P_o) -> dict:
+    """Quantities of App. D for a scalar component g[Q,G] of Psi(q, o) and prune probabilities
+    P_q[Q], P_o[Q,G] (the ones select() reports).
+
+    The estimator is  G_hat = gamma(q) gamma(o,q) g(q,o)  with q drawn from the pruned prompt
+    density P~(q) ~ (1 - P_q) / |Q|, o from pi~(o|q) ~ (1 - P_o) / |O|, and the weights of
+    Eq. 9 / Eq. 12: gamma(o,q) = C_o(q) / (1 - P_o), C_o(q) = mean_o (1 - P_o), likewise for q.
+
+    Per group (App. D.1):  G(q) = mean_o g,  Var_O = mean_o g^2 - G(q)^2,
+        var_o[q] = (C_o / |O|) sum_o g^2 / (1 - P_o) - G(q)^2          (variance of gamma g under pi~)
+        cond_o[q] = mean over pruned-with-positive-probability o of g^2/(1-P_o)  <=  mean_o g^2
+    Prompt level (App. D.2) the same with G(q) in place of g.
+    Total (App. D.3):  term1 = var of gamma(q) G(q);  term2 = E_{q~P~}[gamma(q)^2 var_o[q]]
+        = (C_q / |Q|) sum_q var_o[q] / (1 - P_q);  total = term1 + term2;
+        egamma2 = E_{q~P~}[gamma(q)^2] = (C_q / |Q|) sum_q 1 / (1 - P_q);
+        bound = Var_Q[G(q)] + egamma2 * mean_q Var_O   (Theorem D.1; holds under both conditions).
+    """
+    g = np.asarray(g, dtype=np.float64)
+    Pq = np.asarray(P_q, dtype=np.float64)
+    Po = np.asarray(P_o, dtype=np.float64)
+    Q, G = g.shape
+    Gq = g.mean(axis=1)
+    mean_g2 = (g * g).mean(axis=1)
+    var_O = mean_g2 - Gq * Gq
+    C_o = (1.0 - Po).mean(axis=1)
+    var_o = (C_o / G) * (g * g / (1.0 - Po)).sum(axis=1) - Gq * Gq
+    cond_o = np.ones(Q, dtype=bool)
+    for k in range(Q):
+        sel = Po[k] > 0
+        if sel.any():
+            cond_o[k] = (g[k, sel] ** 2 / (1.0 - Po[k, sel])).mean() <= mean_g2[k]
+    Gbar = Gq.mean()
+    var_Q = (Gq * Gq).mean() - Gbar * Gbar
+    C_q = (1.0 - Pq).mean()
+    term1 = (C_q / Q) * (Gq * Gq / (1.0 - Pq)).sum() - Gbar * Gbar
+    selq = Pq > 0
+    cond_q = bool((Gq[selq] ** 2 / (1.0 - Pq[selq])).mean() <= (Gq * Gq).mean()) if selq.any() else True
+    egamma2 = (C_q / Q) * (1.0 / (1.0 - Pq)).sum()
+    term2 = (C_q / Q) * (var_o / (1.0 - Pq)).sum()
+    return dict(G_q=Gq, var_O=var_O, var_o=var_o, cond_o=cond_o, G_bar=float(Gbar), var_Q=float(var_Q),
+                term1=float(term1), cond_q=cond_q, egamma2=float(egamma2), mean_var_O=float(var_O.mean()),
+                term2=float(term2), total=float(term1 + term2),
+                bound=float(var_Q + egamma2 * var_O.mean()))
+
+
+# ----------------------------------------------------------------------------
 # pi_theta(o_t | q, o_<t): LM-head projection, log-softmax, target gather
 # ----------------------------------------------------------------------------
 def _targets(ids, loss_pos, N):

@@ -760,3 +760,80 @@ def test_token_norm_coef_makes_the_token_level_objective_unbiased():
         c = O.token_norm_coef(s["coef"], cl)
         E += prob * sum(c[q, i] * tok_loss[q][i].sum() for q in range(Q) for i in range(G))
     assert math.isclose(E, direct, rel_tol=1e-10)
+
+
+# ---------------------------------------------------------------- variance of the estimator (App. D)
+def _direct_two_stage_variance(g, Pq, Po):
+    """Var of gamma(q) gamma(o,q) g(q,o) by its definition: enumerate every (q, o) with its probability
+    under the pruned densities."""
+    Q, G = g.shape
+    wq = (1 - Pq) / (1 - Pq).sum()
+    m1 = m2 = 0.0
+    for q in range(Q):
+        wo = (1 - Po[q]) / (1 - Po[q]).sum()
+        gam_q = (1 - Pq).mean() / (1 - Pq[q])
+        for o in range(G):
+            x = gam_q * ((1 - Po[q]).mean() / (1 - Po[q, o])) * g[q, o]
+            m1 += wq[q] * wo[o] * x
+            m2 += wq[q] * wo[o] * x * x
+    return m1, m2 - m1 * m1
+
+
+def test_variance_terms_match_the_definition_and_the_unpruned_case():
+    rng = np.random.default_rng(41)
+    Q, G = 5, 4
+    g = rng.normal(size=(Q, G))
+    # no pruning: weights are 1, every term is a plain population variance, and the law of total
+    # variance makes the total the variance of g over all (q, o)
+    v = O.variance_terms(g, np.zeros(Q), np.zeros((Q, G)))
+    assert np.allclose(v["var_o"], g.var(axis=1), rtol=1e-12) and np.allclose(v["var_O"], g.var(axis=1), rtol=1e-12)
+    assert math.isclose(v["egamma2"], 1.0, rel_tol=1e-15)
+    assert math.isclose(v["total"], g.var(), rel_tol=1e-12) and math.isclose(v["bound"], g.var(), rel_tol=1e-12)
+    # pruning: the decomposition equals the variance computed from the definition, and the estimator is unbiased
+    Pq = np.array([0.5, 0.0, 0.5, 0.0, 0.0])
+    Po = np.where(rng.random((Q, G)) < 0.5, 0.375, 0.0)
+    v = O.variance_terms(g, Pq, Po)
+    mean, var = _direct_two_stage_variance(g, Pq, Po)
+    assert math.isclose(mean, g.mean(), rel_tol=1e-12)
+    assert math.isclose(v["total"], var, rel_tol=1e-11)
+    # prompt-level factor: bottom half pruned with r_q gives the closed form of Theorem D.1
+    for r in (0.3, 0.7, 0.9):
+        Pq = np.array([r] * 3 + [0.0] * 3)
+        e = O.variance_terms(rng.normal(size=(6, 2)), Pq, np.zeros((6, 2)))["egamma2"]
+        assert math.isclose(e, (1 - 0.5 * r) * (1 - 0.5 * r) / (1 - r), rel_tol=1e-12)
+
+
+def test_variance_bound_holds_under_its_conditions_and_can_fail_without_them():
+    rng = np.random.default_rng(43)
+    Q, G = 6, 8
+    Pq = np.array([0.7] * 3 + [0.0] * 3)
+    Po = np.zeros((Q, G)); Po[:, :5] = 0.7
+    # candidates carry small components (the paper's premise: low |A| means small gradient)
+    g = rng.normal(size=(Q, G)); g[:, :5] *= 0.05; g[:3] *= 0.05
+    v = O.variance_terms(g, Pq, Po)
+    assert v["cond_o"].all() and v["cond_q"]
+    assert np.all(v["var_o"] <= v["var_O"] + 1e-15)               # Eq. (completion-level bound)
+    assert v["term1"] <= v["var_Q"] + 1e-15                       # Eq. (prompt-level bound)
+    assert v["total"] <= v["bound"] + 1e-15                       # Theorem D.1
+    # the reverse rule (prune the LARGE components) violates the conditions and the bound
+    g2 = rng.normal(size=(Q, G)); g2[:, 5:] *= 0.05
+    w = O.variance_terms(g2, np.zeros(Q), Po)
+    assert not w["cond_o"].any() and np.all(w["var_o"] > w["var_O"]) and w["total"] > w["bound"]
+
+
+def test_variance_terms_agree_with_sampling():
+    # Monte-Carlo over the two-stage pruned sampling: mean g (unbiased) and the predicted variance
+    rng = np.random.default_rng(47)
+    Q, G = 4, 6
+    g = rng.normal(size=(Q, G))
+    Pq = np.array([0.5, 0.5, 0.0, 0.0])
+    Po = np.zeros((Q, G)); Po[:, ::2] = 0.5
+    v = O.variance_terms(g, Pq, Po)
+    n = 400000
+    qs = rng.choice(Q, size=n, p=(1 - Pq) / (1 - Pq).sum())
+    cdf = np.cumsum((1 - Po) / (1 - Po).sum(axis=1, keepdims=True), axis=1)
+    os_ = (rng.random(n)[:, None] > cdf[qs]).sum(axis=1)
+    x = ((1 - Pq).mean() / (1 - Pq[qs])) * ((1 - Po).mean(axis=1)[qs] / (1 - Po[qs, os_])) * g[qs, os_]
+    se = x.std() / math.sqrt(n)
+    assert abs(x.mean() - g.mean()) < 5 * se
+    assert abs(x.var() - v["total"]) < 0.02 * v["total"]
