@@ -62,6 +62,8 @@ const char* dppo_last_error(void);
  *   coef[k,i]    = gamma_q gamma_o / (|S^q| |S^o_k|): weight of sequence (k,i) in the batch
  *                   loss (mean over retained prompts of the mean over retained completions)
  *   counts[0] = |S^q|, counts[1+k] = |S^o_k| (0 for a pruned prompt)
+ *   prune_q[k], prune_o[k,i] (optional): the prune probability P^q_k, P^o_{k,i} that entered
+ *                   Eq. 18 (0 for non-candidates), whether or not the item was pruned
  *
  * Layout: rewards, u_comp, adv, keep_comp, gamma_o, coef are [Q*G] row-major (prompt
  * major); hist, u_prompt, mean_abs_adv, keep_prompt, gamma_q are [Q]; counts is [1+Q].
@@ -87,7 +89,7 @@ int dppo_select(const dppo_select_params* p,
                 float* adv, float* mean_abs_adv,
                 uint8_t* keep_prompt, uint8_t* keep_comp,
                 float* gamma_q, float* gamma_o, float* coef,
-                int32_t* counts, void* stream);
+                int32_t* counts, float* prune_q /* or NULL */, float* prune_o /* or NULL */, void* stream);
 
 /* dppo_history_update -- Sec. 4.2 Eq. 16 (carry-forward history score).
  * For the n prompts of a batch, prompt b being entry prompt_index[b] of the dataset-wide
@@ -221,6 +223,19 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* p, i
                       float* stats /* or NULL */,
                       void* dH, float* dW,
                       void* ws, size_t ws_bytes, void* stream);
+
+/* dppo_variance_terms -- App. D (variance of the rescaled single-sample estimator
+ * gamma(q) gamma(o,q) g(q,o), q and o drawn from the pruned densities) for one scalar component
+ * g[Q*G] of the gradient term and the prune probabilities reported by dppo_select.
+ *   group_out[4k..4k+3] = { G(q_k) = mean_o g,  Var_O[g],  Var[gamma g] under the pruned completion
+ *                           density (App. D.1),  1.0 if the completion-level condition of the
+ *                           bound holds for the group else 0.0 }
+ *   total_out[10] = { mean of G(q), Var_Q[G(q)], Var[gamma(q) G(q)] (term I), prompt-level
+ *                     condition (1/0), E[gamma(q)^2], mean_q Var_O, term II, term I + term II,
+ *                     Theorem D.1 bound = Var_Q + E[gamma(q)^2] mean_q Var_O, 0 }
+ * All outputs double, computed in float64 in a fixed order (a diagnostic, one workgroup). */
+int dppo_variance_terms(int32_t Q, int32_t G, const float* g, const float* prune_q, const float* prune_o,
+                        double* group_out, double* total_out, void* stream);
 
 /* coef_out[q*G+i] = coef[q*G+i] * G / sum_j comp_len[q*G+j]: weights for DPPO_AGG_TOKEN_SUM. The sum runs
  * over all G completions of the prompt, pruned ones included (their lengths are known before

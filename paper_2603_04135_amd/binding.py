@@ -17,7 +17,7 @@ import torch
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdppo_hip.so")
 _lib = None
 
-EXPORTS = ["dppo_status_str", "dppo_last_error", "dppo_select", "dppo_pack", "dppo_gather_f32", "dppo_token_norm_coef",
+EXPORTS = ["dppo_status_str", "dppo_last_error", "dppo_select", "dppo_pack", "dppo_gather_f32", "dppo_token_norm_coef", "dppo_variance_terms",
            "dppo_workspace_bytes", "dppo_workspace_min_bytes", "dppo_token_logprob", "dppo_loss_fwd_bwd",
            "dppo_timing_enable", "dppo_timing_read", "dppo_history_update"]
 STAGES = ["logits_gemm", "grad_logits", "dh_gemm", "dw_gemm"]
@@ -74,7 +74,9 @@ def load():
     lib.dppo_last_error.restype = c_char_p
     lib.dppo_last_error.argtypes = []
     lib.dppo_select.restype = c_int
-    lib.dppo_select.argtypes = [POINTER(SelectParams)] + [c_void_p] * 13
+    lib.dppo_select.argtypes = [POINTER(SelectParams)] + [c_void_p] * 15
+    lib.dppo_variance_terms.restype = c_int
+    lib.dppo_variance_terms.argtypes = [c_int32, c_int32] + [c_void_p] * 6
     lib.dppo_pack.restype = c_int
     lib.dppo_pack.argtypes = [POINTER(PackParams)] + [c_void_p] * 8 + [c_int64, c_void_p, c_void_p]
     lib.dppo_token_norm_coef.restype = c_int
@@ -153,15 +155,30 @@ def dppo_select(rewards, hist, u_prompt, u_comp, r_q: float, r_o: float, adv_eps
                keep_prompt=torch.empty(Q, dtype=torch.uint8, device=device),
                keep_comp=torch.empty((Q, G), dtype=torch.uint8, device=device),
                gamma_q=torch.empty(Q, **f32), gamma_o=torch.empty((Q, G), **f32),
-               coef=torch.empty((Q, G), **f32), counts=torch.empty(1 + Q, dtype=torch.int32, device=device))
+               coef=torch.empty((Q, G), **f32), counts=torch.empty(1 + Q, dtype=torch.int32, device=device),
+               prune_q=torch.empty(Q, **f32), prune_o=torch.empty((Q, G), **f32))
     p = SelectParams(Q, G, r_q, r_o, adv_eps, std_ddof, bottom_frac, 1 if fixed_count else 0,
                      1 if realised_rate else 0)
     st = lib.dppo_select(ctypes.byref(p), _ptr(rewards), _ptr(hist), _ptr(u_prompt), _ptr(u_comp),
                          _ptr(out["adv"]), _ptr(out["mean_abs_adv"]), _ptr(out["keep_prompt"]),
                          _ptr(out["keep_comp"]), _ptr(out["gamma_q"]), _ptr(out["gamma_o"]), _ptr(out["coef"]),
-                         _ptr(out["counts"]), _stream(device))
+                         _ptr(out["counts"]), _ptr(out["prune_q"]), _ptr(out["prune_o"]), _stream(device))
     _check(st, "dppo_select")
     return out
+
+
+def dppo_variance_terms(g, prune_q, prune_o, device="cuda:0") -> dict:
+    """g [Q,G], prune_q [Q], prune_o [Q,G] -> dict(group[Q,4], total[10]) of float64 device tensors (App. D)."""
+    lib = load()
+    g = _as(g, torch.float32, device)
+    Q, G = g.shape
+    prune_q = _as(prune_q, torch.float32, device)
+    prune_o = _as(prune_o, torch.float32, device)
+    group = torch.empty((Q, 4), dtype=torch.float64, device=device)
+    total = torch.empty(10, dtype=torch.float64, device=device)
+    _check(lib.dppo_variance_terms(Q, G, _ptr(g), _ptr(prune_q), _ptr(prune_o), _ptr(group), _ptr(total),
+                                   _stream(device)), "dppo_variance_terms")
+    return dict(group=group, total=total)
 
 
 def dppo_history_update(hist_table: torch.Tensor, prompt_index, keep_prompt, mean_abs_adv) -> torch.Tensor:

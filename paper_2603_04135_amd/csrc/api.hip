@@ -209,7 +209,8 @@ const char* dppo_last_error(void) { return g_err; }
 
 int dppo_select(const dppo_select_params* p, const float* rewards, const float* hist, const float* u_prompt,
                 const float* u_comp, float* adv, float* mean_abs_adv, uint8_t* keep_prompt, uint8_t* keep_comp,
-                float* gamma_q, float* gamma_o, float* coef, int32_t* counts, void* stream) {
+                float* gamma_q, float* gamma_o, float* coef, int32_t* counts, float* prune_q, float* prune_o,
+                void* stream) {
     if (!p) return fail(DPPO_ERR_INVALID_ARG, "params is NULL");
     if (!rewards || !adv || !mean_abs_adv || !keep_prompt || !keep_comp || !gamma_q || !gamma_o || !coef || !counts)
         return fail(DPPO_ERR_INVALID_ARG, "a required array pointer is NULL");
@@ -225,8 +226,17 @@ int dppo_select(const dppo_select_params* p, const float* rewards, const float* 
         return fail(DPPO_ERR_INVALID_ARG, "fixed_count and realised_rate must be 0 or 1");
     const int n_bottom = (int)std::floor((double)p->bottom_frac * (double)p->Q);
     launch_select(*p, n_bottom, rewards, hist, u_prompt, u_comp, adv, mean_abs_adv, keep_prompt, keep_comp, gamma_q,
-                  gamma_o, coef, counts, (hipStream_t)stream);
+                  gamma_o, coef, counts, prune_q, prune_o, (hipStream_t)stream);
     return check_launch("dppo_select");
+}
+
+int dppo_variance_terms(int32_t Q, int32_t G, const float* g, const float* prune_q, const float* prune_o,
+                        double* group_out, double* total_out, void* stream) {
+    if (Q <= 0 || G <= 0) return fail(DPPO_ERR_SHAPE, "Q and G must be positive (Q=%d G=%d)", Q, G);
+    if (!g || !prune_q || !prune_o || !group_out || !total_out)
+        return fail(DPPO_ERR_INVALID_ARG, "a required array pointer is NULL");
+    launch_variance_terms(Q, G, g, prune_q, prune_o, group_out, total_out, (hipStream_t)stream);
+    return check_launch("dppo_variance_terms");
 }
 
 int dppo_history_update(int32_t n, const int32_t* prompt_index, const uint8_t* keep_prompt,

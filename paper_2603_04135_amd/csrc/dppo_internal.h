@@ -20,7 +20,9 @@ static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 void launch_select(const dppo_select_params& p, int n_bottom, const float* rewards, const float* hist,
                    const float* u_prompt, const float* u_comp, float* adv, float* mean_abs_adv,
                    uint8_t* keep_prompt, uint8_t* keep_comp, float* gamma_q, float* gamma_o,
-                   float* coef, int32_t* counts, hipStream_t st);
+                   float* coef, int32_t* counts, float* prune_q, float* prune_o, hipStream_t st);
+void launch_variance_terms(int32_t Q, int32_t G, const float* g, const float* prune_q, const float* prune_o,
+                           double* group_out, double* total_out, hipStream_t st);
 
 void launch_history_update(int32_t n, const int32_t* prompt_index, const uint8_t* keep_prompt,
                            const float* mean_abs_adv, float* hist_table, int64_t table_size, hipStream_t st);

@@ -108,7 +108,8 @@ __global__ void select_weight_kernel(int Q, int G, int n_bottom, float r_q, floa
                                      int realised_rate, const float* __restrict__ u_comp, uint8_t* keep_prompt,
                                      uint8_t* keep_comp, float* __restrict__ gamma_q,
                                      float* __restrict__ gamma_o, float* __restrict__ coef,
-                                     int32_t* __restrict__ counts) {
+                                     int32_t* __restrict__ counts, float* __restrict__ prune_q,
+                                     float* __restrict__ prune_o) {
     int k = blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= Q) return;
     const int n_q = counts[0];
@@ -147,6 +148,7 @@ __global__ void select_weight_kernel(int Q, int G, int n_bottom, float r_q, floa
     counts[1 + k] = n_o;
     const double gq = kp ? ((double)n_q / (double)Q) / (1.0 - Pq) : 0.0;
     gamma_q[k] = (float)gq;
+    if (prune_q) prune_q[k] = (float)Pq;
     keep_prompt[k] = kp ? 1 : 0;
     for (int i = 0; i < G; ++i) {
         const size_t idx = (size_t)k * G + i;
@@ -159,6 +161,7 @@ __global__ void select_weight_kernel(int Q, int G, int n_bottom, float r_q, floa
         }
         gamma_o[idx] = (float)go;
         coef[idx] = (float)cf;
+        if (prune_o) prune_o[idx] = (float)Po;
         flags[i] = keep ? 1 : 0;
     }
 }
@@ -174,12 +177,65 @@ __global__ void history_update_kernel(int n, const int32_t* __restrict__ prompt_
     if (keep_prompt[b] != 0 && q >= 0 && q < table_size) hist_table[q] = mean_abs_adv[b];
 }
 
+// App. D in float64, fixed order: threads take prompt groups, thread 0 sums over the groups.
+__global__ __launch_bounds__(256) void variance_terms_kernel(int Q, int G, const float* __restrict__ g,
+                                                             const float* __restrict__ prune_q,
+                                                             const float* __restrict__ prune_o,
+                                                             double* __restrict__ group_out,
+                                                             double* __restrict__ total_out) {
+    for (int k = threadIdx.x; k < Q; k += blockDim.x) {
+        const float* gk = g + (size_t)k * G;
+        const float* pk = prune_o + (size_t)k * G;
+        double s1 = 0.0, s2 = 0.0, keep = 0.0, w2 = 0.0, c2 = 0.0;
+        int nc = 0;
+        for (int i = 0; i < G; ++i) {
+            const double x = (double)gk[i], P = (double)pk[i];
+            s1 = s1 + x;
+            s2 = s2 + x * x;
+            keep = keep + (1.0 - P);
+            w2 = w2 + x * x / (1.0 - P);
+            if (P > 0.0) { c2 = c2 + x * x / (1.0 - P); nc += 1; }
+        }
+        const double Gq = s1 / G, m2 = s2 / G, Co = keep / G;
+        group_out[4 * k + 0] = Gq;
+        group_out[4 * k + 1] = m2 - Gq * Gq;
+        group_out[4 * k + 2] = (Co / G) * w2 - Gq * Gq;
+        group_out[4 * k + 3] = (nc == 0 || c2 / nc <= m2) ? 1.0 : 0.0;
+    }
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    double sG = 0.0, sG2 = 0.0, keep = 0.0, wG2 = 0.0, inv = 0.0, sVarO = 0.0, wVar = 0.0, c2 = 0.0;
+    int nc = 0;
+    for (int k = 0; k < Q; ++k) {
+        const double Gq = group_out[4 * k], P = (double)prune_q[k];
+        sG = sG + Gq;
+        sG2 = sG2 + Gq * Gq;
+        keep = keep + (1.0 - P);
+        wG2 = wG2 + Gq * Gq / (1.0 - P);
+        inv = inv + 1.0 / (1.0 - P);
+        sVarO = sVarO + group_out[4 * k + 1];
+        wVar = wVar + group_out[4 * k + 2] / (1.0 - P);
+        if (P > 0.0) { c2 = c2 + Gq * Gq / (1.0 - P); nc += 1; }
+    }
+    const double Gbar = sG / Q, varQ = sG2 / Q - Gbar * Gbar, Cq = keep / Q;
+    const double term1 = (Cq / Q) * wG2 - Gbar * Gbar, eg2 = (Cq / Q) * inv, term2 = (Cq / Q) * wVar;
+    total_out[0] = Gbar; total_out[1] = varQ; total_out[2] = term1;
+    total_out[3] = (nc == 0 || c2 / nc <= sG2 / Q) ? 1.0 : 0.0;
+    total_out[4] = eg2; total_out[5] = sVarO / Q; total_out[6] = term2; total_out[7] = term1 + term2;
+    total_out[8] = varQ + eg2 * (sVarO / Q); total_out[9] = 0.0;
+}
+
 }  // namespace
+
+void launch_variance_terms(int32_t Q, int32_t G, const float* g, const float* prune_q, const float* prune_o,
+                           double* group_out, double* total_out, hipStream_t st) {
+    variance_terms_kernel<<<1, 256, 0, st>>>(Q, G, g, prune_q, prune_o, group_out, total_out);
+}
 
 void launch_select(const dppo_select_params& p, int n_bottom, const float* rewards, const float* hist,
                    const float* u_prompt, const float* u_comp, float* adv, float* mean_abs_adv,
                    uint8_t* keep_prompt, uint8_t* keep_comp, float* gamma_q, float* gamma_o,
-                   float* coef, int32_t* counts, hipStream_t st) {
+                   float* coef, int32_t* counts, float* prune_q, float* prune_o, hipStream_t st) {
     const int threads = 64;
     const int blocks = (p.Q + threads - 1) / threads;
     select_group_kernel<<<blocks, threads, 0, st>>>(p.Q, p.G, (double)p.adv_eps, p.std_ddof, rewards, adv,
@@ -188,7 +244,7 @@ void launch_select(const dppo_select_params& p, int n_bottom, const float* rewar
                                              counts);
     select_weight_kernel<<<blocks, threads, 0, st>>>(p.Q, p.G, n_bottom, p.r_q, p.r_o, p.fixed_count,
                                                      p.realised_rate, u_comp, keep_prompt, keep_comp, gamma_q,
-                                                     gamma_o, coef, counts);
+                                                     gamma_o, coef, counts, prune_q, prune_o);
 }
 
 void launch_history_update(int32_t n, const int32_t* prompt_index, const uint8_t* keep_prompt,

@@ -30,6 +30,7 @@ def _cmp_select(P, rewards, hist, up, uc, r_q, r_o, ddof=1, eps=1e-6, bottom=0.5
     assert np.array_equal(g["counts"], ref["counts"])
     for k in ("adv", "mean_abs_adv", "gamma_q", "gamma_o", "coef"):
         assert np.allclose(g[k], ref[k], rtol=2e-6, atol=1e-9), k
+    assert np.allclose(g["prune_q"], ref["P_q"], rtol=2e-7, atol=0) and np.allclose(g["prune_o"], ref["P_o"], rtol=2e-7, atol=0)
     return ref, g
 
 
@@ -104,6 +105,50 @@ def test_history_update_matches_oracle(lib):
     want = O.history_update(rb.hist, np.arange(rb.wl.Q), o["keep_prompt"], o["mean_abs_adv"].astype(np.float32))
     assert np.allclose(t.cpu().numpy(), want, rtol=2e-6, atol=1e-9)
     assert np.array_equal(t.cpu().numpy()[o["keep_prompt"] == 0], rb.hist[o["keep_prompt"] == 0])
+
+
+@pytest.mark.parametrize("name", ["small", "qwen3_4b", "stress"])
+def test_variance_terms_match_oracle(lib, name):
+    # App. D: g = a stand-in gradient component that is small where |A| is small (the paper's premise)
+    rb = WL.make_rollout(name)
+    wl = rb.wl
+    sel = lib.dppo_select(rb.rewards, rb.hist, rb.u_prompt, rb.u_comp, wl.r_q, wl.r_o, device=DEV)
+    adv = sel["adv"].cpu().numpy()
+    rng = np.random.default_rng(3)
+    for g in ((adv * rng.normal(1.0, 0.3, size=adv.shape)).astype(np.float32),
+              rng.normal(size=adv.shape).astype(np.float32)):
+        got = lib.dppo_variance_terms(g, sel["prune_q"], sel["prune_o"], device=DEV)
+        ref = O.variance_terms(g, sel["prune_q"].cpu().numpy(), sel["prune_o"].cpu().numpy())
+        grp, tot = got["group"].cpu().numpy(), got["total"].cpu().numpy()
+        scale = float((g.astype(np.float64) ** 2).mean())
+        for col, key in enumerate(("G_q", "var_O", "var_o")):
+            assert np.allclose(grp[:, col], ref[key], rtol=1e-9, atol=1e-12 * scale), key
+        # the 0/1 condition flags may differ only where the two sides of the inequality tie to rounding
+        assert (grp[:, 3] != ref["cond_o"]).mean() <= 0.01
+        for idx, key in ((0, "G_bar"), (1, "var_Q"), (2, "term1"), (4, "egamma2"), (5, "mean_var_O"), (6, "term2"),
+                         (7, "total"), (8, "bound")):
+            assert abs(tot[idx] - ref[key]) <= 1e-9 * abs(ref[key]) + 1e-12 * scale, key
+        assert tot[3] == float(ref["cond_q"])
+    # the closed-form prompt factor of Theorem D.1 with half the prompts candidates
+    closed = (1 - 0.5 * wl.r_q) * (1 - 0.5 * wl.r_q) / (1 - wl.r_q)
+    assert abs(tot[4] - closed) <= 1e-6 * closed + (0 if wl.Q % 2 == 0 else 0.05)
+
+
+def test_batch_estimator_is_unbiased_over_sampled_masks(lib):
+    # Monte-Carlo over masks with the selection kernel itself: E[sum_i coef_i g_i] = mean g (Eq. 13)
+    rb = WL.make_rollout("small")
+    wl = rb.wl
+    rng = np.random.default_rng(5)
+    g = torch.as_tensor(rng.normal(1.0, 1.0, size=rb.rewards.shape).astype(np.float32), device=DEV)
+    vals = []
+    for _ in range(400):
+        up = rng.random(wl.Q, dtype=np.float32)
+        uc = rng.random((wl.Q, wl.G), dtype=np.float32)
+        sel = lib.dppo_select(rb.rewards, rb.hist, up, uc, wl.r_q, wl.r_o, device=DEV)
+        vals.append((sel["coef"].double() * g.double()).sum())
+    vals = torch.stack(vals).cpu().numpy()
+    se = vals.std() / np.sqrt(len(vals))
+    assert abs(vals.mean() - float(g.double().mean())) < 5 * se
 
 
 def test_select_rejects_bad_arguments(lib):

@@ -43,12 +43,12 @@ def test_host_side_validation_launches_nothing(lib):
     from paper_2603_04135_amd.binding import HeadShape, LossParams, PackParams, SelectParams
     one = ctypes.c_void_p(256)   # never dereferenced: validation fails first
     sp = SelectParams(4, 4, 1.0, 0.5, 1e-6, 1, 0.5, 0, 1)       # r_q outside [0,1)
-    assert lib.dppo_select(ctypes.byref(sp), *([one] * 12), None) == 1
+    assert lib.dppo_select(ctypes.byref(sp), *([one] * 14), None) == 1
     assert b"[0,1)" in lib.dppo_last_error()
     sp = SelectParams(4, 1, 0.5, 0.5, 1e-6, 1, 0.5, 0, 1)       # sample std of one completion
-    assert lib.dppo_select(ctypes.byref(sp), *([one] * 12), None) == 2
+    assert lib.dppo_select(ctypes.byref(sp), *([one] * 14), None) == 2
     sp = SelectParams(4, 4, 0.5, 0.5, 1e-6, 1, 0.5, 0, 1)
-    assert lib.dppo_select(ctypes.byref(sp), None, *([one] * 11), None) == 1
+    assert lib.dppo_select(ctypes.byref(sp), None, *([one] * 13), None) == 1
     pp = PackParams(0, 16, 4, 0)
     assert lib.dppo_pack(ctypes.byref(pp), *([one] * 8), 10, one, None) == 2
     pp = PackParams(4, 16, 0, 0)
@@ -69,6 +69,8 @@ def test_host_side_validation_launches_nothing(lib):
     lp = LossParams(0.2, 0.2, 0.04, 0, 0, 2, 0)          # unknown ratio level
     assert lib.dppo_loss_fwd_bwd(ctypes.byref(hs), ctypes.byref(lp), 3, *([one] * 15), one, 1 << 30, None) == 1
     assert lib.dppo_token_norm_coef(0, 4, one, one, one, None) == 2
+    assert lib.dppo_variance_terms(4, 0, one, one, one, one, one, None) == 2
+    assert lib.dppo_variance_terms(4, 4, one, None, one, one, one, None) == 1
 
 
 def test_workspace_sizes(lib):
