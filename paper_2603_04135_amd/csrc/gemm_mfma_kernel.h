@@ -7,10 +7,12 @@
 //
 // One workgroup owns a BM x BN output tile. K is streamed in slices of BK elements that go from
 // global memory straight into LDS (global_load_lds_dwordx4: no register staging, no ds_write),
-// STAGES slices deep. Each wavefront owns a (BM/WGM) x (BN/WGN) sub-tile of 32x32x16 MFMA blocks
-// and reads its operands one 16-wide k-step ahead into a second register set. The single barrier
-// per slice sits before the LAST k-step of the slice: the first operands of the next slice are
-// fetched, and the freed buffer is refilled, while the current slice still computes.
+// STAGES slices deep. Each wavefront owns a (BM/WGM) x (BN/WGN) sub-tile of 16x16x32 MFMA blocks
+// (with random operands the chip is power-limited, and a register-only loop of 16x16x32
+// instructions sustains 15 % more than one of 32x32x16: 2.02 against 1.76 PFLOP/s) and reads its
+// operands one 32-wide k-step ahead. The single barrier per slice sits before the LAST k-step of
+// the slice: the first operands of the next slice are fetched, and the freed buffer is refilled,
+// while the current slice still computes.
 //
 // LDS layout: a tile row is BK*2 bytes; its 16-byte chunks are XOR-swizzled so that the 16 lanes
 // a ds_read_b128 serves per cycle (16 consecutive tile rows, same k-chunk) fall into 16 different
@@ -31,7 +33,7 @@ namespace mfma {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) char lds_char;
@@ -48,8 +50,12 @@ struct TileCtx {
     char* smem;
 };
 
-// Row of accumulator element j (0..15) of a 32x32 MFMA block, relative to the block.
-__device__ __forceinline__ int acc_row(int lane, int j) { return 8 * (j >> 2) + 4 * (lane >> 5) + (j & 3); }
+// 16x16x32 MFMA register layout: operand lane l holds row (A) or column (B) l % 16 and the 8
+// k-values 8 * (l / 16) .. + 7; accumulator lane l holds column l % 16 and the 4 rows acc_row(l, j).
+constexpr int MB = 16;    // rows / columns of an MFMA block
+constexpr int MK = 32;    // k-values of one MFMA
+__device__ __forceinline__ int acc_row(int lane, int j) { return 4 * (lane >> 4) + j; }
+__device__ __forceinline__ int acc_col(int lane) { return lane & 15; }
 
 #define DPPO_GPTR(p) ((const void __attribute__((address_space(1)))*)(p))
 #define DPPO_LPTR(p) ((void __attribute__((address_space(3)))*)(p))
@@ -89,8 +95,8 @@ struct PipeCfg {
     static constexpr int SWZ = SWZ_, SPREAD = SPREAD_;
     static constexpr int NW = WGM * WGN, NT = NW * 64;
     static constexpr int WTM = BM / WGM, WTN = BN / WGN;
-    static constexpr int MI = WTM / 32, NI = WTN / 32;
-    static constexpr int KK = BK / 16;
+    static constexpr int MI = WTM / MB, NI = WTN / MB;
+    static constexpr int KK = BK / MK;
     static constexpr int ROWB = BK * 2;
     static constexpr int CPR = BK / 8;
     static constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB;
@@ -104,12 +110,11 @@ struct PipeCfg {
     static_assert(SPREAD_STEPS <= KK, "spread");
     static constexpr int LPSTEP = (LPS + SPREAD_STEPS - 1) / SPREAD_STEPS;
     static_assert(LPS % SPREAD_STEPS == 0, "loads per step");
-    static_assert(BK == 32 || BK == 64, "BK");
+    static_assert(BK == 32 || BK == 64 || BK == 128, "BK");
     static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile vs wavefront count");
     static_assert((STAGES - 1) * LPS <= 63, "vmcnt range");
-    static_assert(KK % 2 == 0, "operand double buffer");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS");
-    static_assert(MI + NI <= MI * NI && LPSTEP <= MI * NI, "one read / load slot per MFMA of a k-step");
+    static_assert(NI >= 3 && NI <= MI && LPSTEP <= MI, "read and load slots of a k-step");
 };
 
 // Layout of the A operand (template parameter AM):
@@ -124,8 +129,9 @@ struct PipeCfg {
 // by tile touches BK widely separated rows per slice and new pages at every slice.
 // A_BLK_KM: the slice sits in LDS as BK rows of BM elements and the MFMA operand (8 consecutive k
 // for one m per lane) is gathered by two transposing reads. The 16-byte chunks of a k-row are
-// XOR-swizzled by 4 * (k & 3) so that the 4 k-rows x 32 bytes a group of 16 lanes touches, and
-// the two groups of a half-wave, fall into different banks.
+// XOR-swizzled by 4 * (k & 3) + 2 * ((k >> 3) & 1) so that the 4 k-rows x 32 bytes a group of 16
+// lanes touches, and the two groups of a half-wave (same columns, k-rows 8 apart), fall into
+// different banks.
 enum { A_ROWS = 0, A_BLK_ROWS = 1, A_BLK_KM = 2 };
 constexpr int BLK_R = 64, BLK_C = 256;
 __host__ __device__ __forceinline__ size_t blk_offset(int64_t r, int64_t c, int64_t ld) {
@@ -172,10 +178,10 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
         const int ii = isA ? i : i - Cfg::A_LD;
         const int ci = (ii * Cfg::NW + wave) * 64 + lane;
         if (A_KM && isA) {
-            static_assert(!A_KM || (Cfg::BK == BLK_R && Cfg::BM == BLK_C), "block shape = slice shape");
+            static_assert(!A_KM || (BLK_R % Cfg::BK == 0 && Cfg::BM == BLK_C), "a slice stays inside one block");
             constexpr int CPR_A = Cfg::BM / 8;
             const int krow = ci / CPR_A, pc = ci % CPR_A;
-            const int mc = pc ^ (4 * (krow & 3));
+            const int mc = pc ^ (4 * (krow & 3) + 2 * ((krow >> 3) & 1));
             pl[i] = A + blk_offset(krow, bm0 + mc * 8, lda);
             continue;
         }
@@ -195,7 +201,7 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
     auto issue_loads = [&](int buf, int kt, int first, int count) {
         char* dst = smem + buf * Cfg::STAGE_BYTES + wave * 1024;
         const size_t koff = (size_t)kt * Cfg::BK;
-        const size_t koff_a = A_KM ? (size_t)kt * BLK_R * (size_t)lda
+        const size_t koff_a = A_KM ? blk_offset((int64_t)kt * Cfg::BK, 0, lda)
                               : AM == A_BLK_ROWS ? blk_offset(0, (int64_t)kt * Cfg::BK, lda) : koff;
 #pragma unroll
         for (int i = 0; i < LPS; ++i) {
@@ -207,61 +213,55 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
         }
     };
 
-    const int frag_row = lane & 31, frag_half = lane >> 5;
+    // Operand registers. Block mi of A is needed by NI consecutive MFMAs of a k-step and is dead
+    // after them, so the blocks 0 .. MI-2 are single-buffered: the next k-step's block is read into
+    // the same registers right after its last use. The last block would then be read at the very
+    // end of the k-step, so it alone has two register sets and is read first. B blocks are needed
+    // throughout a k-step and are double-buffered.
+    const int frag_row = lane & 15, frag_q = lane >> 4;
     const int sw = swz<CPR, Cfg::SWZ>(frag_row);
     const int a_base = (wave_m * Cfg::WTM + frag_row) * ROWB;
     const int b_base = Cfg::A_BYTES + (wave_n * Cfg::WTN + frag_row) * ROWB;
-    bf16x8 af[2][MI], bfr[2][NI];
-    // A_KM: byte offset, inside the A slice, of this lane's 8-byte source row for block mi at k-step 0
-    // (first of the two transposing reads; the second is 4 k-rows further on).
+    bf16x8 af[MI + 1], bfr[2][NI];
+    auto a_slot = [](int mi, int parity) { return mi == MI - 1 ? MI - 1 + parity : mi; };
+    // A_BLK_KM: byte offset, inside the A slice, of this lane's 8-byte source row for block mi at
+    // k-step 0 (first of the two transposing reads; the second is 4 k-rows further on). A group of
+    // 16 lanes reads 4 k-rows x 32 bytes; groups 0,1 (2,3) of a half-wave differ in bit 3 of k.
     constexpr int ROWB_A = Cfg::BM * 2;
     int a_km[MI];
     if (A_KM) {
-        static_assert(!A_KM || (Cfg::WTM % 128 == 0 && MI <= 4), "swizzle of the [K, M] slice");
-        const int s16 = lane & 15, grp = (lane >> 4) & 1;
-        const int krow = 8 * frag_half + (s16 >> 2);
+        static_assert(!A_KM || (Cfg::WTM % 128 == 0 && MI <= 8), "swizzle of the [K, M] slice");
+        const int s16 = lane & 15;
+        const int xl = 2 * (s16 >> 2) + (frag_q & 1);            // (swizzle term of the k-row) / 2
+        const int lane_off = (8 * frag_q + (s16 >> 2)) * ROWB_A + wave_m * (Cfg::WTM * 2) + ((s16 & 3) >> 1) * 16 +
+                             (s16 & 1) * 8;
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi) {
-            const int chunk = wave_m * (Cfg::WTM / 8) + 4 * (mi ^ (s16 >> 2)) + 2 * grp + ((s16 & 3) >> 1);
-            a_km[mi] = krow * ROWB_A + chunk * 16 + (s16 & 1) * 8;
-        }
+        for (int mi = 0; mi < MI; ++mi) a_km[mi] = lane_off + 32 * (mi ^ xl);
     }
-    auto read_a = [&](int set, const char* st, int kk, int mi) {
+    auto read_a = [&](int slot, const char* st, int kk, int mi) {
         if (A_KM) {
-            const lds_char* p = (const lds_char*)(st + a_km[mi] + kk * 16 * ROWB_A);
+            const lds_char* p = (const lds_char*)(st + a_km[mi] + kk * MK * ROWB_A);
             const s16x4 lo = lds_read_tr16(p);
             const s16x4 hi = lds_read_tr16(p + 4 * ROWB_A);
             const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            af[set][mi] = __builtin_bit_cast(bf16x8, v);
+            af[slot] = __builtin_bit_cast(bf16x8, v);
         } else {
-            const int kc_off = ((kk * 2 + frag_half) ^ sw) << 4;
-            af[set][mi] = *reinterpret_cast<const bf16x8*>(st + a_base + mi * 32 * ROWB + kc_off);
+            const int kc_off = ((kk * 4 + frag_q) ^ sw) << 4;
+            af[slot] = *reinterpret_cast<const bf16x8*>(st + a_base + mi * MB * ROWB + kc_off);
         }
     };
-    auto read_frags = [&](int set, int buf, int kk) {
-        const char* st = smem + buf * Cfg::STAGE_BYTES;
-        const int kc_off = ((kk * 2 + frag_half) ^ sw) << 4;
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) read_a(set, st, kk, mi);
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-            bfr[set][ni] = *reinterpret_cast<const bf16x8*>(st + b_base + ni * 32 * ROWB + kc_off);
+    auto read_b = [&](int set, const char* st, int kk, int ni) {
+        const int kc_off = ((kk * 4 + frag_q) ^ sw) << 4;
+        bfr[set][ni] = *reinterpret_cast<const bf16x8*>(st + b_base + ni * MB * ROWB + kc_off);
     };
 
-    auto read_one = [&](int set, int buf, int kk, bool isA, int idx) {
-        const char* st = smem + buf * Cfg::STAGE_BYTES;
-        const int kc_off = ((kk * 2 + frag_half) ^ sw) << 4;
-        if (isA) read_a(set, st, kk, idx);
-        else bfr[set][idx] = *reinterpret_cast<const bf16x8*>(st + b_base + idx * 32 * ROWB + kc_off);
-    };
-
-    f32x16 acc[MI][NI];
+    f32x4 acc[MI][NI];
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-            for (int j = 0; j < 16; ++j) acc[mi][ni][j] = 0.0f;
+            for (int j = 0; j < 4; ++j) acc[mi][ni][j] = 0.0f;
 
     const int KT = K / Cfg::BK;
 #pragma unroll
@@ -269,21 +269,26 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
         if (s < KT) issue_loads(s, s, 0, LPS);
     if (KT >= STAGES) wait_loads_then_barrier<(STAGES - 1) * LPS>();
     else wait_loads_then_barrier<0>();
-    read_frags(0, 0, 0);
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) read_a(a_slot(mi, 0), smem, 0, mi);
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) read_b(0, smem, 0, ni);
 
     // Slice kt+STAGES is fetched into the buffer of slice kt. That buffer is released by the barrier
     // at the last k-step of slice kt; its loads are issued in the SS k-steps that follow (the last
     // step of slice kt and the first SS-1 steps of slice kt+1).
     // One slice = KK k-steps. STEADY iterations (1 <= kt, kt + STAGES < KT) have every condition
-    // resolved at compile time, so the whole slice is straight-line code.
+    // resolved at compile time, so the whole slice is straight-line code. PAR = parity of the
+    // slice's first k-step (which B register set it computes from); always 0 when KK is even.
     int buf = 0;
-    auto slice = [&](int kt, auto steady_tag) {
+    auto slice = [&](int kt, auto steady_tag, auto parity_tag) __attribute__((always_inline)) {
         constexpr bool STEADY = decltype(steady_tag)::value;
+        constexpr int PAR = decltype(parity_tag)::value;
         const int nbuf = (buf + 1 == STAGES) ? 0 : buf + 1;
         const int pbuf = (buf == 0) ? STAGES - 1 : buf - 1;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-            const int cur = kk & 1, nxt = cur ^ 1;
+            const int cur = (kk + PAR) & 1, nxt = cur ^ 1;
             bool loads_here = false, reads_here = false;
             int load_buf = 0, load_kt = 0, load_first = 0, read_buf = 0, read_kk = 0;
             if (kk == KK - 1) {
@@ -303,30 +308,44 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
             }
             {
                 // Instruction order of a k-step, pinned by scheduling barriers (left to itself the
-                // compiler sinks the reads next to their use and exposes the LDS latency):
-                // MFMA q, then operand read q of the next k-step (A0 B0 B1 .. then the remaining A
-                // blocks) and one global load.
+                // compiler sinks the reads next to their use and exposes the LDS latency). MFMA q
+                // works on block (q / NI, q % NI); behind it, in the row of A block mi = q / NI:
+                //   first MFMA of the step: the next step's last A block (into its spare registers),
+                //   2nd MFMA of rows 0 .. NI-1: the next step's B block mi,
+                //   3rd MFMA of rows 0 .. LPSTEP-1: one global load,
+                //   last MFMA of rows 0 .. MI-2: the next step's A block mi, over the one just used.
+                const char* rst = smem + read_buf * Cfg::STAGE_BYTES;
 #pragma unroll
                 for (int q = 0; q < MI * NI; ++q) {
                     const int mi = q / NI, ni = q % NI;
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][mi], bfr[cur][ni], acc[mi][ni], 0, 0, 0);
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[a_slot(mi, cur)], bfr[cur][ni], acc[mi][ni], 0, 0, 0);
                     __builtin_amdgcn_sched_barrier(0);
-                    if (reads_here && q < MI + NI) {
-                        const int which = q == 0 ? 0 : (q <= NI ? -q : q - NI);   // >= 0: A block, < 0: B block -which-1
-                        if (which >= 0) read_one(nxt, read_buf, read_kk, true, which);
-                        else read_one(nxt, read_buf, read_kk, false, -which - 1);
+                    if (reads_here) {
+                        if (q == 0) read_a(a_slot(MI - 1, nxt), rst, read_kk, MI - 1);
+                        if (ni == 1 && mi < NI) read_b(nxt, rst, read_kk, mi);
+                        if (ni == NI - 1 && mi < MI - 1) read_a(mi, rst, read_kk, mi);
                     }
-                    if (loads_here && q < LPSTEP) issue_loads(load_buf, load_kt, load_first + q, 1);
+                    if (loads_here && ni == 2 && mi < LPSTEP) issue_loads(load_buf, load_kt, load_first + mi, 1);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
         }
         buf = nbuf;
     };
+    typedef std::integral_constant<int, 0> P0;
+    typedef std::integral_constant<int, 1> P1;
     int kt = 0;
-    if (KT > 0) { slice(0, std::false_type{}); kt = 1; }
-    for (; kt + STAGES < KT; ++kt) slice(kt, std::true_type{});
-    for (; kt < KT; ++kt) slice(kt, std::false_type{});
+    if (KT > 0) { slice(0, std::false_type{}, P0{}); kt = 1; }
+    if (KK & 1) {
+        // odd KK: the register-set parity alternates from slice to slice; kt stays odd here, so
+        // slices go in pairs of parity (1, 0)
+        for (; kt + 1 + STAGES < KT; kt += 2) { slice(kt, std::true_type{}, P1{}); slice(kt + 1, std::true_type{}, P0{}); }
+        for (; kt + 1 < KT; kt += 2) { slice(kt, std::false_type{}, P1{}); slice(kt + 1, std::false_type{}, P0{}); }
+        if (kt < KT) slice(kt, std::false_type{}, P1{});
+    } else {
+        for (; kt + STAGES < KT; ++kt) slice(kt, std::true_type{}, P0{});
+        for (; kt < KT; ++kt) slice(kt, std::false_type{}, P0{});
+    }
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
     TileCtx c;
@@ -347,17 +366,17 @@ struct EpiStore {
     float* Cf; uint16_t* Cb; int64_t ldc; int accumulate; const int32_t* row_map; int64_t row_base;
 
     template <class Cfg>
-    __device__ __forceinline__ void run(f32x16 (&acc)[Cfg::MI][Cfg::NI], const TileCtx& c) const {
+    __device__ __forceinline__ void run(f32x4 (&acc)[Cfg::MI][Cfg::NI], const TileCtx& c) const {
 #pragma unroll
         for (int mi = 0; mi < Cfg::MI; ++mi)
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const int row = c.m0 + mi * 32 + acc_row(c.lane, j);
+            for (int j = 0; j < 4; ++j) {
+                const int row = c.m0 + mi * MB + acc_row(c.lane, j);
                 if (row >= c.M) continue;
                 const int64_t orow = (KIND == 1 && row_map) ? (int64_t)row_map[row_base + row] : (int64_t)row;
 #pragma unroll
                 for (int ni = 0; ni < Cfg::NI; ++ni) {
-                    const int col = c.n0 + ni * 32 + (c.lane & 31);
+                    const int col = c.n0 + ni * MB + acc_col(c.lane);
                     if (col >= c.N) continue;
                     const float v = acc[mi][ni][j];
                     const size_t idx = (size_t)orow * ldc + col;
@@ -379,6 +398,15 @@ typedef EpiStore<1> EpiStoreDH;
 
 constexpr float LOG2E = 1.4426950408889634f;
 
+// Stores the BN x BM tile staged in LDS as [token][vocabulary row] (pitch ZPITCH bytes, 2-byte
+// elements) to the blocked chunk dst (pitch ld elements): 16-byte vectors, 32 lanes per 512-byte row.
+template <class Cfg>
+__device__ __forceinline__ void store_staged_row(const TileCtx& c, uint16_t* dst, int64_t ld, int r, int ch) {
+    constexpr int ZPITCH = Cfg::BM * 2 + 16;
+    const u32x4 val = *reinterpret_cast<const u32x4*>(c.smem + r * ZPITCH + ch * 16);
+    *reinterpret_cast<u32x4*>(dst + blk_offset(c.bn0 + r, c.bm0 + ch * 8, ld)) = val;
+}
+
 // Rows = vocabulary entries, columns = tokens.
 template <bool STORE_Z>
 struct EpiLogits {
@@ -386,7 +414,7 @@ struct EpiLogits {
     _Float16* Z16; int64_t ldz; int Vp;   // Z16: [n_cp, ldz] in BLK_R x BLK_C blocks (blk_offset)
 
     template <class Cfg>
-    __device__ __forceinline__ void run(f32x16 (&acc)[Cfg::MI][Cfg::NI], const TileCtx& c) const {
+    __device__ __forceinline__ void run(f32x4 (&acc)[Cfg::MI][Cfg::NI], const TileCtx& c) const {
         constexpr int MI = Cfg::MI, NI = Cfg::NI;
         const float NEG_INF = -__builtin_inff();
         // LDS (free after the main loop's closing barrier): the tile's logits as fp16, laid out
@@ -398,25 +426,24 @@ struct EpiLogits {
         if (STORE_Z) {
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni) {
-                const int tok = c.wave_n * Cfg::WTN + ni * 32 + (c.lane & 31);
+                const int tok = c.wave_n * Cfg::WTN + ni * MB + acc_col(c.lane);
 #pragma unroll
-                for (int mi = 0; mi < MI; ++mi)
+                for (int mi = 0; mi < MI; ++mi) {
+                    const int vloc = c.wave_m * Cfg::WTM + mi * MB + acc_row(c.lane, 0);
+                    f16x4 h;
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int vloc = c.wave_m * Cfg::WTM + mi * 32 + 8 * g + 4 * (c.lane >> 5);
-                        f16x4 h;
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            float z = acc[mi][ni][4 * g + q];
-                            z = fminf(fmaxf(z, -65504.0f), 65504.0f);
-                            h[q] = (_Float16)z;
-                        }
-                        *reinterpret_cast<f16x4*>(c.smem + tok * ZPITCH + vloc * 2) = h;
+                    for (int q = 0; q < 4; ++q) {
+                        float z = acc[mi][ni][q];
+                        z = fminf(fmaxf(z, -65504.0f), 65504.0f);
+                        h[q] = (_Float16)z;
                     }
+                    *reinterpret_cast<f16x4*>(c.smem + tok * ZPITCH + vloc * 2) = h;
+                }
             }
             __syncthreads();
         }
-        // per-lane running max over this wavefront's vocabulary rows, per token column
+        // running max over this wavefront's vocabulary rows, per token column: in-lane over the
+        // blocks, then across the four lane groups that hold the column's other rows
         float mx[NI], mref[NI], sm[NI];
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni) {
@@ -424,11 +451,12 @@ struct EpiLogits {
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const int row = c.m0 + mi * 32 + acc_row(c.lane, j);
+                for (int j = 0; j < 4; ++j) {
+                    const int row = c.m0 + mi * MB + acc_row(c.lane, j);
                     const float v = row < c.M ? acc[mi][ni][j] : NEG_INF;
                     m = fmaxf(m, v);
                 }
+            m = fmaxf(m, __shfl_xor(m, 16, 64));
             m = fmaxf(m, __shfl_xor(m, 32, 64));
             mx[ni] = m;
             mref[ni] = (m == NEG_INF) ? 0.0f : m;
@@ -441,38 +469,37 @@ struct EpiLogits {
         constexpr int CH = Cfg::BM / 8;                     // 16-byte chunks per row
         constexpr int ROWS_PER_PASS = Cfg::NT / CH;
         constexpr int PASSES = Cfg::BN / ROWS_PER_PASS;
-        constexpr int TERMS = MI * NI * 16;                 // exponentials per lane
+        constexpr int TERMS = MI * NI * 4;                  // exponentials per lane
         static_assert(TERMS % PASSES == 0, "terms per store pass");
         constexpr int TPP = TERMS / PASSES;
         const int ch = c.tid % CH;
-        const int v0 = c.bm0 + ch * 8;
         // ldz is a multiple of BM = BLK_C (checked by the launcher), so every column of the tile has a
         // home in Z16 and the stores need no branch, which would undo the interleaving.
         static_assert(!STORE_Z || (Cfg::BM == BLK_C && Cfg::BN % BLK_R == 0), "tile = whole blocks");
 #pragma unroll
         for (int it = 0; it < PASSES; ++it) {
-            if (STORE_Z) {
-                const int r = c.tid / CH + it * ROWS_PER_PASS;
-                const u32x4 val = *reinterpret_cast<const u32x4*>(c.smem + r * ZPITCH + ch * 16);
-                *reinterpret_cast<u32x4*>(Z16 + blk_offset(c.bn0 + r, v0, ldz)) = val;
-            }
+            if (STORE_Z)
+                store_staged_row<Cfg>(c, reinterpret_cast<uint16_t*>(Z16), ldz, c.tid / CH + it * ROWS_PER_PASS, ch);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int e = 0; e < TPP; ++e) {
                 const int idx = it * TPP + e;
-                const int ni = idx / (MI * 16), mi = (idx / 16) % MI, j = idx % 16;
-                const int row = c.m0 + mi * 32 + acc_row(c.lane, j);
+                const int ni = idx / (MI * 4), mi = (idx / 4) % MI, j = idx % 4;
+                const int row = c.m0 + mi * MB + acc_row(c.lane, j);
                 const float ex = __builtin_amdgcn_exp2f((acc[mi][ni][j] - mref[ni]) * LOG2E);
                 sm[ni] += row < c.M ? ex : 0.0f;
             }
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni) sm[ni] += __shfl_xor(sm[ni], 32, 64);
-        if (c.lane < 32) {
+        for (int ni = 0; ni < NI; ++ni) {
+            sm[ni] += __shfl_xor(sm[ni], 16, 64);
+            sm[ni] += __shfl_xor(sm[ni], 32, 64);
+        }
+        if (c.lane < MB) {
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni)
-                red[c.wave_m * Cfg::BN + c.wave_n * Cfg::WTN + ni * 32 + c.lane] = make_float2(mx[ni], sm[ni]);
+                red[c.wave_m * Cfg::BN + c.wave_n * Cfg::WTN + ni * MB + c.lane] = make_float2(mx[ni], sm[ni]);
         }
         __syncthreads();
         for (int t = c.tid; t < Cfg::BN; t += Cfg::NT) {
@@ -503,44 +530,39 @@ struct EpiLogitsGrad {
     uint16_t* G; int64_t ldg; int64_t n_cp; int V;
 
     template <class Cfg>
-    __device__ __forceinline__ void run(f32x16 (&acc)[Cfg::MI][Cfg::NI], const TileCtx& c) const {
+    __device__ __forceinline__ void run(f32x4 (&acc)[Cfg::MI][Cfg::NI], const TileCtx& c) const {
         static_assert(Cfg::BM == BLK_C && Cfg::BN % BLK_R == 0, "tile = whole blocks");
         constexpr int ZPITCH = Cfg::BM * 2 + 16;
 #pragma unroll
         for (int ni = 0; ni < Cfg::NI; ++ni) {
-            const int tok = c.wave_n * Cfg::WTN + ni * 32 + (c.lane & 31);
+            const int tok = c.wave_n * Cfg::WTN + ni * MB + acc_col(c.lane);
             const int64_t col = c.bn0 + tok;
             const bool col_ok = col < n_cp;
             const int yt = col_ok ? y[col] : -1;
             const float l = col_ok ? lse[col] : 0.0f;
             const float cn = col_ok ? cvec[col] : 0.0f;
 #pragma unroll
-            for (int mi = 0; mi < Cfg::MI; ++mi)
+            for (int mi = 0; mi < Cfg::MI; ++mi) {
+                const int vloc = c.wave_m * Cfg::WTM + mi * MB + acc_row(c.lane, 0);
+                bf16x4 h;
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int vloc = c.wave_m * Cfg::WTM + mi * 32 + 8 * g + 4 * (c.lane >> 5);
-                    bf16x4 h;
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const int v = c.bm0 + vloc + q;
-                        const float p = __builtin_amdgcn_exp2f((acc[mi][ni][4 * g + q] - l) * LOG2E);
-                        float gv = cn * ((v == yt ? 1.0f : 0.0f) - p);
-                        gv = v < V ? gv : 0.0f;
-                        const __bf16 b = (__bf16)gv;   // scalar copy: reading h[q] back right after writing it miscompiles
-                        h[q] = b;
-                    }
-                    *reinterpret_cast<bf16x4*>(c.smem + tok * ZPITCH + vloc * 2) = h;
+                for (int q = 0; q < 4; ++q) {
+                    const int v = c.bm0 + vloc + q;
+                    const float p = __builtin_amdgcn_exp2f((acc[mi][ni][q] - l) * LOG2E);
+                    float gv = cn * ((v == yt ? 1.0f : 0.0f) - p);
+                    gv = v < V ? gv : 0.0f;
+                    const __bf16 b = (__bf16)gv;   // scalar copy: reading h[q] back right after writing it miscompiles
+                    h[q] = b;
                 }
+                *reinterpret_cast<bf16x4*>(c.smem + tok * ZPITCH + vloc * 2) = h;
+            }
         }
         __syncthreads();
         constexpr int CH = Cfg::BM / 8;
         constexpr int ROWS_PER_PASS = Cfg::NT / CH;
         const int ch = c.tid % CH;
 #pragma unroll 4
-        for (int r = c.tid / CH; r < Cfg::BN; r += ROWS_PER_PASS) {
-            const u32x4 val = *reinterpret_cast<const u32x4*>(c.smem + r * ZPITCH + ch * 16);
-            *reinterpret_cast<u32x4*>(G + blk_offset(c.bn0 + r, c.bm0 + ch * 8, ldg)) = val;
-        }
+        for (int r = c.tid / CH; r < Cfg::BN; r += ROWS_PER_PASS) store_staged_row<Cfg>(c, G, ldg, r, ch);
     }
 
     template <class Cfg>
