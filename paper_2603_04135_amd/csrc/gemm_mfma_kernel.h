@@ -14,11 +14,15 @@
 // the slice: the first operands of the next slice are fetched, and the freed buffer is refilled,
 // while the current slice still computes.
 //
-// LDS layout: a tile row is BK*2 bytes; its 16-byte chunks are XOR-swizzled so that the 16 lanes
-// a ds_read_b128 serves per cycle (16 consecutive tile rows, same k-chunk) fall into 16 different
-// 16-byte bank groups of the 64-bank LDS. A global_load_lds instruction always writes 64 lanes x
-// 16 bytes contiguously, so the swizzle is applied on the global-address side: each lane fetches
-// the chunk that belongs at the LDS position it will be written to.
+// LDS layout: a tile row is BK*2 bytes; its 16-byte chunks are XOR-swizzled so that the lanes a
+// ds_read_b128 serves in one cycle fall into 16 different 16-byte bank groups of the 64-bank LDS.
+// Measured with the bank-conflict counter: a ds_read_b128 is served 16 lanes per cycle, and the
+// lanes that go together are {0-7, 24-31}, {8-15, 16-23}, {32-39, 56-63}, {40-47, 48-55}. With the
+// 16x16x32 operand layout (lane l: tile row l % 16, k-chunk l / 16) these are tile rows 0-7 at
+// chunk c with rows 8-15 at chunk c ^ 1, which the plain swizzle chunk ^ (row & 7) keeps apart
+// (kind 0; the bank-conflict counter reads 0). A global_load_lds instruction always writes 64
+// lanes x 16 bytes contiguously, so the swizzle is applied on the global-address side: each lane
+// fetches the chunk that belongs at the LDS position it will be written to.
 //
 // Workgroup ids are remapped so that the workgroups resident on one XCD (ids congruent mod 8)
 // cover a compact GROUP_M x n block of tiles and share operand panels in that XCD's L2.
@@ -78,8 +82,8 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const lds_char* __restrict__ p) {
 }
 
 // XOR term of the LDS swizzle: logical 16-byte chunk kc of tile row `row` lives at physical chunk
-// kc ^ swz(row). Kind 3 (BK = 64, 8 chunks per row): (row & 7) ^ ((row >> 3) & 1); kinds 0..2:
-// (row >> kind) & (CPR - 1) (kind 2 is the conflict-free choice for BK = 32).
+// kc ^ swz(row). Kinds 0..2: (row >> kind) & (CPR - 1) (kind 0 is the conflict-free choice for
+// BK = 64, kind 2 for BK = 32); kind 3: (row & 7) ^ ((row >> 3) & 1).
 template <int CPR, int SWZ> __device__ __forceinline__ int swz(int row) {
     if (SWZ == 3) return ((row & 7) ^ ((row >> 3) & 1)) & (CPR - 1);
     return (row >> SWZ) & (CPR - 1);
