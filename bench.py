@@ -85,7 +85,7 @@ def main() -> int:
                     help="also run one 1 GiB device-to-device copy (reference point for HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no sharding, no collectives)"
+        print("bench.py: this library runs on ONE GPU; --gpus %d is not supported (no sharding, no collectives)"
               % args.gpus, file=sys.stderr)
         return 2
 

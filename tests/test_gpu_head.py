@@ -1,6 +1,6 @@
 """GPU parity of dppo_token_logprob and dppo_loss_fwd_bwd against the CPU oracle.
 
-Tolerances (from the benchmark spec of this library): per-token log-prob abs err <= 2e-3
+Tolerances: per-token log-prob abs err <= 2e-3
 (bf16 inputs, fp32 accumulation), loss rel err <= 1e-3, dH and dW relative Frobenius
 error <= 1e-2. The float32 data type is held to 1e-4 / 1e-5 / 1e-4 instead."""
 import dataclasses
