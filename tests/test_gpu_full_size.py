@@ -119,6 +119,19 @@ def test_whole_batch_sampled_against_oracle(lib, name):
     dW = out["dW"]
     col = dW.sum(dim=0, dtype=torch.float64)                            # softmax gradients sum to zero over V
     assert float(col.abs().max()) <= 2e-2 * float(dW.abs().sum(dim=0, dtype=torch.float64).max())
+    # logits are bilinear in (H, W): <H, dH> = sum_{n,v} G[n,v] z[n,v] = <W, dW>; ties the whole dW to dH,
+    # whose rows the oracle checked above
+    def inner(a, b, step=1 << 15):
+        acc = torch.zeros((), dtype=torch.float64, device=DEV)
+        mag = torch.zeros((), dtype=torch.float64, device=DEV)
+        for i in range(0, a.shape[0], step):
+            prod = a[i:i + step].double() * b[i:i + step].double()
+            acc += prod.sum()
+            mag += prod.abs().sum()
+        return float(acc), float(mag)
+    h_dh, h_mag = inner(H, out["dH"])
+    w_dw, w_mag = inner(W, dW)
+    assert abs(h_dh - w_dw) <= 2e-3 * max(h_mag, w_mag)
     stats = out["stats"].cpu().numpy()
     assert stats[2] == N and 0.0 < stats[1] < 1.0 and stats[0] > 0.0
     del out, H, W, dW
