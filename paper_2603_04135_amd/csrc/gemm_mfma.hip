@@ -5,10 +5,10 @@ namespace dppo {
 namespace {
 using namespace mfma;
 
-// 256x256x64 tile, 2x4 wavefronts (128x64 each), 2 slices in flight, all loads of a slice issued in
-// the k-step that frees its buffer, bands of 4 tile rows. The blocked chunk layout (64 x 256 element
-// blocks) is tied to this tile.
-typedef PipeCfg<256, 256, 64, 2, 4, 2, 0, 1, 4> CfgBig;
+// 256x256x64 tile, 2x4 wavefronts (128x64 each), 3 A slices and 2 B slices in flight (all 160 KB of
+// LDS), all loads of a slice issued in the k-step that frees its buffers, bands of 4 tile rows. The
+// blocked chunk layout (64 x 256 element blocks) is tied to this tile.
+typedef PipeCfg<256, 256, 64, 2, 4, 2, 0, 1, 4, 1> CfgBig;
 
 // Dynamic LDS of a kernel: the operand slices, or the epilogue's staging area if that is larger.
 template <class Cfg, class Epi>

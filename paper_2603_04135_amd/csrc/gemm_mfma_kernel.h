@@ -89,11 +89,15 @@ template <int CPR, int SWZ> __device__ __forceinline__ int swz(int row) {
     return (row >> SWZ) & (CPR - 1);
 }
 
-// BM x BN x BK tile, WGM x WGN wavefronts, STAGES slices in flight, swizzle kind SWZ; the loads of
-// a slice are issued over SPREAD consecutive k-steps; GROUP_M tile rows form one band of the tile
-// walk.
-template <int BM_, int BN_, int BK_, int WGM_, int WGN_, int STAGES_, int SWZ_, int SPREAD_, int GROUP_M_>
+// BM x BN x BK tile, WGM x WGN wavefronts, STAGES slices of B and STAGES + AX slices of A in
+// flight (A is the operand that streams from HBM in all three GEMMs of the path, B the one that
+// stays cache-resident; with 2 + 1 stages of 32 KB A slices and 2 of B the 160 KB of LDS are used
+// up and the A loads get two slice times to land instead of one), swizzle kind SWZ; SPREAD must be
+// 1 (all loads of a slice are issued in the k-step that frees their buffers); GROUP_M tile rows
+// form one band of the tile walk.
+template <int BM_, int BN_, int BK_, int WGM_, int WGN_, int STAGES_, int SWZ_, int SPREAD_, int GROUP_M_, int AX_ = 0>
 struct PipeCfg {
+    static constexpr int SA = STAGES_ + AX_, SB = STAGES_;   // ring depths of the A and B slices
     static constexpr int GROUP_M = GROUP_M_;   // tile rows per band of the tile walk
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WGM = WGM_, WGN = WGN_, STAGES = STAGES_;
     static constexpr int SWZ = SWZ_, SPREAD = SPREAD_;
@@ -104,21 +108,22 @@ struct PipeCfg {
     static constexpr int ROWB = BK * 2;
     static constexpr int CPR = BK / 8;
     static constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB;
-    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-    static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
+    static constexpr int B_RING = SA * A_BYTES;               // LDS offset of the B ring
+    static constexpr int LDS_BYTES = SA * A_BYTES + SB * B_BYTES;
     static constexpr int A_LD = A_BYTES / 1024 / NW;
     static constexpr int B_LD = B_BYTES / 1024 / NW;
     static constexpr int LPS = A_LD + B_LD;
     // loads of one slice are issued in SPREAD_STEPS consecutive k-steps, starting right after the barrier
     static constexpr int SPREAD_STEPS = SPREAD < 1 ? 1 : SPREAD;
-    static_assert(SPREAD_STEPS <= KK, "spread");
+    static_assert(SPREAD_STEPS == 1, "spread");
+    static_assert(AX_ == 0 || AX_ == 1, "extra A stages");
     static constexpr int LPSTEP = (LPS + SPREAD_STEPS - 1) / SPREAD_STEPS;
     static_assert(LPS % SPREAD_STEPS == 0, "loads per step");
     static_assert(BK == 32 || BK == 64 || BK == 128, "BK");
     static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile vs wavefront count");
-    static_assert((STAGES - 1) * LPS <= 63, "vmcnt range");
+    static_assert(SA * LPS <= 63, "vmcnt range");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS");
-    static_assert(NI >= 3 && NI <= MI && LPSTEP <= MI, "read and load slots of a k-step");
+    static_assert(NI >= 3 && NI <= MI && LPS <= MI, "read and load slots of a k-step");
 };
 
 // Layout of the A operand (template parameter AM):
@@ -148,8 +153,8 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
                                                           int N, int K, int tiles_m, int tiles_n, Epi epi) {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     constexpr bool A_KM = AM == A_BLK_KM;
-    constexpr int MI = Cfg::MI, NI = Cfg::NI, KK = Cfg::KK, STAGES = Cfg::STAGES, LPS = Cfg::LPS;
-    constexpr int ROWB = Cfg::ROWB, CPR = Cfg::CPR, LPSTEP = Cfg::LPSTEP, SS = Cfg::SPREAD_STEPS;
+    constexpr int MI = Cfg::MI, NI = Cfg::NI, KK = Cfg::KK, LPS = Cfg::LPS;
+    constexpr int ROWB = Cfg::ROWB, CPR = Cfg::CPR;
 
     const int total = tiles_m * tiles_n;
     int logical;
@@ -201,20 +206,18 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
         }
         pl[i] = (isA ? A : B) + (size_t)r * (isA ? lda : ldb) + kc * 8;
     }
-    // issues loads [first, first+count) of slice kt into buffer buf
-    auto issue_loads = [&](int buf, int kt, int first, int count) {
-        char* dst = smem + buf * Cfg::STAGE_BYTES + wave * 1024;
+    // Issues load i of slice kt: i < B_LD is a B load into B-ring buffer bufb, the others are A loads
+    // into A-ring buffer bufa. B goes first, so that at the next barrier "all but the newest A_LD
+    // loads" means: this slice's B loads have landed, its A loads (due one slice later) may not have.
+    auto issue_load = [&](int bufa, int bufb, int kt, int i) {
         const size_t koff = (size_t)kt * Cfg::BK;
         const size_t koff_a = A_KM ? blk_offset((int64_t)kt * Cfg::BK, 0, lda)
                               : AM == A_BLK_ROWS ? blk_offset(0, (int64_t)kt * Cfg::BK, lda) : koff;
-#pragma unroll
-        for (int i = 0; i < LPS; ++i) {
-            if (i < first || i >= first + count) continue;
-            const bool isA = i < Cfg::A_LD;
-            const int ii = isA ? i : i - Cfg::A_LD;
-            __builtin_amdgcn_global_load_lds(DPPO_GPTR(pl[i] + (isA ? koff_a : koff)),
-                                             DPPO_LPTR(dst + (isA ? 0 : Cfg::A_BYTES) + ii * Cfg::NW * 1024), 16, 0, 0);
-        }
+        const bool isA = i >= Cfg::B_LD;
+        const int ii = isA ? i - Cfg::B_LD : i;
+        char* dst = smem + (isA ? bufa * Cfg::A_BYTES : Cfg::B_RING + bufb * Cfg::B_BYTES) + (ii * Cfg::NW + wave) * 1024;
+        const uint16_t* src = isA ? pl[ii] + koff_a : pl[Cfg::A_LD + ii] + koff;
+        __builtin_amdgcn_global_load_lds(DPPO_GPTR(src), DPPO_LPTR(dst), 16, 0, 0);
     };
 
     // Operand registers. Block mi of A is needed by NI consecutive MFMAs of a k-step and is dead
@@ -225,7 +228,7 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
     const int frag_row = lane & 15, frag_q = lane >> 4;
     const int sw = swz<CPR, Cfg::SWZ>(frag_row);
     const int a_base = (wave_m * Cfg::WTM + frag_row) * ROWB;
-    const int b_base = Cfg::A_BYTES + (wave_n * Cfg::WTN + frag_row) * ROWB;
+    const int b_base = (wave_n * Cfg::WTN + frag_row) * ROWB;
     bf16x8 af[MI + 1], bfr[2][NI];
     auto a_slot = [](int mi, int parity) { return mi == MI - 1 ? MI - 1 + parity : mi; };
     // A_BLK_KM: byte offset, inside the A slice, of this lane's 8-byte source row for block mi at
@@ -268,47 +271,58 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
             for (int j = 0; j < 4; ++j) acc[mi][ni][j] = 0.0f;
 
     const int KT = K / Cfg::BK;
+    constexpr int SA = Cfg::SA, SB = Cfg::SB, A_LD = Cfg::A_LD, B_LD = Cfg::B_LD;
+    // Slice kt has its A part in A-ring buffer kt % SA and its B part in B-ring buffer kt % SB. The
+    // barrier at the last k-step of slice kt releases both buffers of slice kt, and the loads
+    // [B of slice kt+SB, A of slice kt+SA] are issued behind it, in that order. Prologue: the same
+    // groups for the virtual slices -SA .. -1.
 #pragma unroll
-    for (int s = 0; s < STAGES; ++s)
-        if (s < KT) issue_loads(s, s, 0, LPS);
-    if (KT >= STAGES) wait_loads_then_barrier<(STAGES - 1) * LPS>();
+    for (int j = -SA; j < 0; ++j) {
+        if (j + SB >= 0 && j + SB < KT) {
+#pragma unroll
+            for (int i = 0; i < B_LD; ++i) issue_load(0, (j + SB) % SB, j + SB, i);
+        }
+        if (j + SA < KT) {
+#pragma unroll
+            for (int i = 0; i < A_LD; ++i) issue_load((j + SA) % SA, 0, j + SA, B_LD + i);
+        }
+    }
+    // loads issued behind B of slice 0: A of slices 1 .. SA-1 and B of slices 1 .. SB-1
+    if (KT >= SA) wait_loads_then_barrier<(SA - 1) * A_LD + (SB - 1) * B_LD>();
     else wait_loads_then_barrier<0>();
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) read_a(a_slot(mi, 0), smem, 0, mi);
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni) read_b(0, smem, 0, ni);
+    for (int ni = 0; ni < NI; ++ni) read_b(0, smem + Cfg::B_RING, 0, ni);
 
-    // Slice kt+STAGES is fetched into the buffer of slice kt. That buffer is released by the barrier
-    // at the last k-step of slice kt; its loads are issued in the SS k-steps that follow (the last
-    // step of slice kt and the first SS-1 steps of slice kt+1).
-    // One slice = KK k-steps. STEADY iterations (1 <= kt, kt + STAGES < KT) have every condition
+    // One slice = KK k-steps. STEADY iterations (1 <= kt, kt + SA < KT) have every condition
     // resolved at compile time, so the whole slice is straight-line code. PAR = parity of the
     // slice's first k-step (which B register set it computes from); always 0 when KK is even.
-    int buf = 0;
+    // At the barrier of slice kt the data of slice kt+1 must have landed; behind its B part were
+    // issued (in steady state) SB-2 whole groups and, if the A ring is deeper, the A part of the
+    // group that brought it.
+    constexpr int STEADY_PENDING = (SB - 2) * LPS + (SA > SB ? A_LD : 0);
+    int bufa = 0, bufb = 0;
     auto slice = [&](int kt, auto steady_tag, auto parity_tag) __attribute__((always_inline)) {
         constexpr bool STEADY = decltype(steady_tag)::value;
         constexpr int PAR = decltype(parity_tag)::value;
-        const int nbuf = (buf + 1 == STAGES) ? 0 : buf + 1;
-        const int pbuf = (buf == 0) ? STAGES - 1 : buf - 1;
+        const int nbufa = (bufa + 1 == SA) ? 0 : bufa + 1;
+        const int nbufb = (bufb + 1 == SB) ? 0 : bufb + 1;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
             const int cur = (kk + PAR) & 1, nxt = cur ^ 1;
-            bool loads_here = false, reads_here = false;
-            int load_buf = 0, load_kt = 0, load_first = 0, read_buf = 0, read_kk = 0;
+            bool loads_a = false, loads_b = false, reads_here = false;
+            int read_bufa = 0, read_bufb = 0, read_kk = 0;
             if (kk == KK - 1) {
                 if (STEADY || kt + 1 < KT) {
-                    // loads issued after slice kt+1: slices kt+2 .. kt+STAGES-1 (complete); the first
-                    // part of slice kt+STAGES is issued below
-                    if (STEADY || kt + STAGES <= KT) wait_loads_then_barrier<(STAGES - 2) * LPS>();
+                    if (STEADY) wait_loads_then_barrier<STEADY_PENDING>();
                     else wait_loads_then_barrier<0>();
-                    if (STEADY || kt + STAGES < KT) { load_buf = buf; load_kt = kt + STAGES; load_first = 0; loads_here = true; }
-                    read_buf = nbuf; read_kk = 0; reads_here = true;
+                    loads_b = STEADY || kt + SB < KT;
+                    loads_a = STEADY || kt + SA < KT;
+                    read_bufa = nbufa; read_bufb = nbufb; read_kk = 0; reads_here = true;
                 }
             } else {
-                if (SS > 1 && kk + 1 < SS && (STEADY || (kt >= 1 && kt - 1 + STAGES < KT))) {
-                    load_buf = pbuf; load_kt = kt - 1 + STAGES; load_first = (kk + 1) * LPSTEP; loads_here = true;
-                }
-                read_buf = buf; read_kk = kk + 1; reads_here = true;
+                read_bufa = bufa; read_bufb = bufb; read_kk = kk + 1; reads_here = true;
             }
             {
                 // Instruction order of a k-step, pinned by scheduling barriers (left to itself the
@@ -316,25 +330,29 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
                 // works on block (q / NI, q % NI); behind it, in the row of A block mi = q / NI:
                 //   first MFMA of the step: the next step's last A block (into its spare registers),
                 //   2nd MFMA of rows 0 .. NI-1: the next step's B block mi,
-                //   3rd MFMA of rows 0 .. LPSTEP-1: one global load,
+                //   3rd MFMA of rows 0 .. LPS-1: one global load (B loads first),
                 //   last MFMA of rows 0 .. MI-2: the next step's A block mi, over the one just used.
-                const char* rst = smem + read_buf * Cfg::STAGE_BYTES;
+                const char* rsa = smem + read_bufa * Cfg::A_BYTES;
+                const char* rsb = smem + Cfg::B_RING + read_bufb * Cfg::B_BYTES;
 #pragma unroll
                 for (int q = 0; q < MI * NI; ++q) {
                     const int mi = q / NI, ni = q % NI;
                     acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[a_slot(mi, cur)], bfr[cur][ni], acc[mi][ni], 0, 0, 0);
                     __builtin_amdgcn_sched_barrier(0);
                     if (reads_here) {
-                        if (q == 0) read_a(a_slot(MI - 1, nxt), rst, read_kk, MI - 1);
-                        if (ni == 1 && mi < NI) read_b(nxt, rst, read_kk, mi);
-                        if (ni == NI - 1 && mi < MI - 1) read_a(mi, rst, read_kk, mi);
+                        if (q == 0) read_a(a_slot(MI - 1, nxt), rsa, read_kk, MI - 1);
+                        if (ni == 1 && mi < NI) read_b(nxt, rsb, read_kk, mi);
+                        if (ni == NI - 1 && mi < MI - 1) read_a(mi, rsa, read_kk, mi);
                     }
-                    if (loads_here && ni == 2 && mi < LPSTEP) issue_loads(load_buf, load_kt, load_first + mi, 1);
+                    if (ni == 2 && mi < LPS) {
+                        if (mi < B_LD) { if (loads_b) issue_load(bufa, bufb, kt + SB, mi); }
+                        else if (loads_a) issue_load(bufa, bufb, kt + SA, mi);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
         }
-        buf = nbuf;
+        bufa = nbufa; bufb = nbufb;
     };
     typedef std::integral_constant<int, 0> P0;
     typedef std::integral_constant<int, 1> P1;
@@ -343,11 +361,11 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
     if (KK & 1) {
         // odd KK: the register-set parity alternates from slice to slice; kt stays odd here, so
         // slices go in pairs of parity (1, 0)
-        for (; kt + 1 + STAGES < KT; kt += 2) { slice(kt, std::true_type{}, P1{}); slice(kt + 1, std::true_type{}, P0{}); }
+        for (; kt + 1 + SA < KT; kt += 2) { slice(kt, std::true_type{}, P1{}); slice(kt + 1, std::true_type{}, P0{}); }
         for (; kt + 1 < KT; kt += 2) { slice(kt, std::false_type{}, P1{}); slice(kt + 1, std::false_type{}, P0{}); }
         if (kt < KT) slice(kt, std::false_type{}, P1{});
     } else {
-        for (; kt + STAGES < KT; ++kt) slice(kt, std::true_type{}, P0{});
+        for (; kt + SA < KT; ++kt) slice(kt, std::true_type{}, P0{});
         for (; kt < KT; ++kt) slice(kt, std::false_type{}, P0{});
     }
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
