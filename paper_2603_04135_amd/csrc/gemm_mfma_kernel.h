@@ -7,11 +7,11 @@
 //
 // One workgroup owns a BM x BN output tile. K is streamed in slices of BK elements that go from
 // global memory straight into LDS (global_load_lds_dwordx4: no register staging, no ds_write),
-// STAGES slices deep. Each wavefront owns a (BM/WGM) x (BN/WGN) sub-tile of 16x16x32 MFMA blocks
+// into one ring of slices per operand (the A ring may be one slice deeper). Each wavefront owns a (BM/WGM) x (BN/WGN) sub-tile of 16x16x32 MFMA blocks
 // (with random operands the chip is power-limited, and a register-only loop of 16x16x32
 // instructions sustains 15 % more than one of 32x32x16: 2.02 against 1.76 PFLOP/s) and reads its
 // operands one 32-wide k-step ahead. The single barrier per slice sits before the LAST k-step of
-// the slice: the first operands of the next slice are fetched, and the freed buffer is refilled,
+// the slice: the first operands of the next slice are fetched, and the freed buffers are refilled,
 // while the current slice still computes.
 //
 // LDS layout: a tile row is BK*2 bytes; its 16-byte chunks are XOR-swizzled so that the lanes a
@@ -113,12 +113,8 @@ struct PipeCfg {
     static constexpr int A_LD = A_BYTES / 1024 / NW;
     static constexpr int B_LD = B_BYTES / 1024 / NW;
     static constexpr int LPS = A_LD + B_LD;
-    // loads of one slice are issued in SPREAD_STEPS consecutive k-steps, starting right after the barrier
-    static constexpr int SPREAD_STEPS = SPREAD < 1 ? 1 : SPREAD;
-    static_assert(SPREAD_STEPS == 1, "spread");
+    static_assert(SPREAD == 1, "spread");
     static_assert(AX_ == 0 || AX_ == 1, "extra A stages");
-    static constexpr int LPSTEP = (LPS + SPREAD_STEPS - 1) / SPREAD_STEPS;
-    static_assert(LPS % SPREAD_STEPS == 0, "loads per step");
     static_assert(BK == 32 || BK == 64 || BK == 128, "BK");
     static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile vs wavefront count");
     static_assert(SA * LPS <= 63, "vmcnt range");
