@@ -422,7 +422,9 @@ template <class Cfg>
 __device__ __forceinline__ void store_staged_row(const TileCtx& c, uint16_t* dst, int64_t ld, int r, int ch) {
     constexpr int ZPITCH = Cfg::BM * 2 + 16;
     const u32x4 val = *reinterpret_cast<const u32x4*>(c.smem + r * ZPITCH + ch * 16);
-    *reinterpret_cast<u32x4*>(dst + blk_offset(c.bn0 + r, c.bm0 + ch * 8, ld)) = val;
+    // streaming store: the chunk (10 GB) is not read again before it has left every cache, and a
+    // regular store would evict the operand panels the other tiles of the group share in L2
+    __builtin_nontemporal_store(val, reinterpret_cast<u32x4*>(dst + blk_offset(c.bn0 + r, c.bm0 + ch * 8, ld)));
 }
 
 // Rows = vocabulary entries, columns = tokens.

@@ -259,7 +259,7 @@ __global__ __launch_bounds__(256) void grad_logits_blocked_kernel(void* ZG, int3
         const float l = lse[n], cn = cvec[n];
         const int yt = y[n];
         char* p = base + (r * BC + cc * 8) * 2;
-        const f16x8 z = *reinterpret_cast<const f16x8*>(p);
+        const f16x8 z = __builtin_nontemporal_load(reinterpret_cast<const f16x8*>(p));   // read once
         bf16x8 g;
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
@@ -270,7 +270,7 @@ __global__ __launch_bounds__(256) void grad_logits_blocked_kernel(void* ZG, int3
             const __bf16 b = (__bf16)gv;   // keep the scalar: reading g[q] back right after writing it miscompiles
             g[q] = b;
         }
-        *reinterpret_cast<bf16x8*>(p) = g;
+        __builtin_nontemporal_store(g, reinterpret_cast<bf16x8*>(p));
     }
 }
 
