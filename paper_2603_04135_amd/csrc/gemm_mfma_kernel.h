@@ -7,7 +7,8 @@
 //
 // One workgroup owns a BM x BN output tile. K is streamed in slices of BK elements that go from
 // global memory straight into LDS (global_load_lds_dwordx4: no register staging, no ds_write),
-// into one ring of slices per operand (the A ring may be one slice deeper). Each wavefront owns a (BM/WGM) x (BN/WGN) sub-tile of 16x16x32 MFMA blocks
+// into one ring of slices per operand (the A ring may be one slice deeper). Each wavefront
+// owns a (BM/WGM) x (BN/WGN) sub-tile of 16x16x32 MFMA blocks
 // (with random operands the chip is power-limited, and a register-only loop of 16x16x32
 // instructions sustains 15 % more than one of 32x32x16: 2.02 against 1.76 PFLOP/s) and reads its
 // operands one 32-wide k-step ahead. The single barrier per slice sits before the LAST k-step of
@@ -464,53 +465,60 @@ struct EpiLogits {
         }
         // running max over this wavefront's vocabulary rows, per token column: in-lane over the
         // blocks, then across the four lane groups that hold the column's other rows
+        // Only the last row of tiles has vocabulary rows beyond M; every other tile takes the
+        // branch that is compiled without the row masks.
         float mx[NI], mref[NI], sm[NI];
+        auto reduce = [&](auto full_tag) __attribute__((always_inline)) {
+            constexpr bool FULL = decltype(full_tag)::value;
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni) {
-            float m = NEG_INF;
+            for (int ni = 0; ni < NI; ++ni) {
+                float m = NEG_INF;
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
+                for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int row = c.m0 + mi * MB + acc_row(c.lane, j);
-                    const float v = row < c.M ? acc[mi][ni][j] : NEG_INF;
-                    m = fmaxf(m, v);
-                }
-            m = fmaxf(m, __shfl_xor(m, 16, 64));
-            m = fmaxf(m, __shfl_xor(m, 32, 64));
-            mx[ni] = m;
-            mref[ni] = (m == NEG_INF) ? 0.0f : m;
-            sm[ni] = 0.0f;
-        }
-        // The store path of a compute unit takes a 1 KB store instruction only every few dozen
-        // cycles, so the 16-byte stores of the staged tile (32 lanes x 16 bytes = one 512-byte token
-        // row piece, two rows per instruction) are interleaved with the exponentials of the sum:
-        // the arithmetic runs while the store queue drains.
-        constexpr int CH = Cfg::BM / 8;                     // 16-byte chunks per row
-        constexpr int ROWS_PER_PASS = Cfg::NT / CH;
-        constexpr int PASSES = Cfg::BN / ROWS_PER_PASS;
-        constexpr int TERMS = MI * NI * 4;                  // exponentials per lane
-        static_assert(TERMS % PASSES == 0, "terms per store pass");
-        constexpr int TPP = TERMS / PASSES;
-        const int ch = c.tid % CH;
-        // ldz is a multiple of BM = BLK_C (checked by the launcher), so every column of the tile has a
-        // home in Z16 and the stores need no branch, which would undo the interleaving.
-        static_assert(!STORE_Z || (Cfg::BM == BLK_C && Cfg::BN % BLK_R == 0), "tile = whole blocks");
-#pragma unroll
-        for (int it = 0; it < PASSES; ++it) {
-            if (STORE_Z)
-                store_staged_row<Cfg>(c, reinterpret_cast<uint16_t*>(Z16), ldz, c.tid / CH + it * ROWS_PER_PASS, ch);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int e = 0; e < TPP; ++e) {
-                const int idx = it * TPP + e;
-                const int ni = idx / (MI * 4), mi = (idx / 4) % MI, j = idx % 4;
-                const int row = c.m0 + mi * MB + acc_row(c.lane, j);
-                const float ex = __builtin_amdgcn_exp2f((acc[mi][ni][j] - mref[ni]) * LOG2E);
-                sm[ni] += row < c.M ? ex : 0.0f;
+                    for (int j = 0; j < 4; ++j) {
+                        const int row = c.m0 + mi * MB + acc_row(c.lane, j);
+                        const float v = (FULL || row < c.M) ? acc[mi][ni][j] : NEG_INF;
+                        m = fmaxf(m, v);
+                    }
+                m = fmaxf(m, __shfl_xor(m, 16, 64));
+                m = fmaxf(m, __shfl_xor(m, 32, 64));
+                mx[ni] = m;
+                mref[ni] = (m == NEG_INF) ? 0.0f : m;
+                sm[ni] = 0.0f;
             }
-            __builtin_amdgcn_sched_barrier(0);
-        }
+            // The store path of a compute unit takes a 1 KB store instruction only every few dozen
+            // cycles, so the 16-byte stores of the staged tile (32 lanes x 16 bytes = one 512-byte token
+            // row piece, two rows per instruction) are interleaved with the exponentials of the sum:
+            // the arithmetic runs while the store queue drains.
+            constexpr int CH = Cfg::BM / 8;                     // 16-byte chunks per row
+            constexpr int ROWS_PER_PASS = Cfg::NT / CH;
+            constexpr int PASSES = Cfg::BN / ROWS_PER_PASS;
+            constexpr int TERMS = MI * NI * 4;                  // exponentials per lane
+            static_assert(TERMS % PASSES == 0, "terms per store pass");
+            constexpr int TPP = TERMS / PASSES;
+            const int ch = c.tid % CH;
+            // ldz is a multiple of BM = BLK_C (checked by the launcher), so every column of the tile has a
+            // home in Z16 and the stores need no branch, which would undo the interleaving.
+            static_assert(!STORE_Z || (Cfg::BM == BLK_C && Cfg::BN % BLK_R == 0), "tile = whole blocks");
+#pragma unroll
+            for (int it = 0; it < PASSES; ++it) {
+                if (STORE_Z)
+                    store_staged_row<Cfg>(c, reinterpret_cast<uint16_t*>(Z16), ldz, c.tid / CH + it * ROWS_PER_PASS, ch);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int e = 0; e < TPP; ++e) {
+                    const int idx = it * TPP + e;
+                    const int ni = idx / (MI * 4), mi = (idx / 4) % MI, j = idx % 4;
+                    const int row = c.m0 + mi * MB + acc_row(c.lane, j);
+                    const float ex = __builtin_amdgcn_exp2f((acc[mi][ni][j] - mref[ni]) * LOG2E);
+                    sm[ni] += (FULL || row < c.M) ? ex : 0.0f;
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        if (c.bm0 + Cfg::BM <= c.M) reduce(std::true_type{});
+        else reduce(std::false_type{});
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni) {
             sm[ni] += __shfl_xor(sm[ni], 16, 64);
