@@ -378,39 +378,76 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
 // ---------------------------------------------------------------------------------------
 // Epilogues
 // ---------------------------------------------------------------------------------------
-// Plain store of the accumulators. KIND 0 (dW): float output, overwrite or accumulate.
-// KIND 1 (dH): bf16 output, optional row scatter through row_map.
+// Store of the accumulators. KIND 0 (dW): float output, overwrite or accumulate. KIND 1 (dH):
+// bf16 output, optional row scatter through row_map.
+// dW is a read-modify-write of 256 KB per tile; straight from the accumulator layout it would be
+// 4-byte accesses in 64-byte runs, so the tile goes through LDS (free after the main loop) in two
+// halves of BM/2 rows = the rows of one wavefront row, and leaves as 16-byte accesses that cover
+// whole 1 KB output rows. The sums are the same numbers in the same order.
 template <int KIND>
 struct EpiStore {
     float* Cf; uint16_t* Cb; int64_t ldc; int accumulate; const int32_t* row_map; int64_t row_base;
 
     template <class Cfg>
     __device__ __forceinline__ void run(f32x4 (&acc)[Cfg::MI][Cfg::NI], const TileCtx& c) const {
+        if (KIND == 0) {
+            static_assert(KIND != 0 || Cfg::WGM == 2, "one half of the tile per wavefront row");
+            typedef float f32x4v __attribute__((ext_vector_type(4)));
+            constexpr int PITCH = Cfg::BN * 4 + 16;           // bytes per staged row
+            constexpr int HALF = Cfg::BM / 2;
+            constexpr int VPR = Cfg::BN / 4;                   // float4 per row
+            constexpr int RPP = Cfg::NT / VPR;                 // rows per pass
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                if (c.wave_m == h) {
+#pragma unroll
+                    for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+                        for (int ni = 0; ni < Cfg::NI; ++ni)
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                const int r = mi * MB + acc_row(c.lane, j);
+                                const int col = c.wave_n * Cfg::WTN + ni * MB + acc_col(c.lane);
+                                *reinterpret_cast<float*>(c.smem + r * PITCH + col * 4) = acc[mi][ni][j];
+                            }
+                }
+                __syncthreads();
+                const int cv = c.tid % VPR;
+                const int col = c.bn0 + cv * 4;
+#pragma unroll 4
+                for (int r = c.tid / VPR; r < HALF; r += RPP) {
+                    const int row = c.bm0 + h * HALF + r;
+                    if (row < c.M && col < c.N) {
+                        f32x4v v = *reinterpret_cast<const f32x4v*>(c.smem + r * PITCH + cv * 16);
+                        f32x4v* dst = reinterpret_cast<f32x4v*>(Cf + (size_t)row * ldc + col);
+                        if (accumulate) v += *dst;
+                        *dst = v;
+                    }
+                }
+                __syncthreads();
+            }
+            return;
+        }
 #pragma unroll
         for (int mi = 0; mi < Cfg::MI; ++mi)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int row = c.m0 + mi * MB + acc_row(c.lane, j);
                 if (row >= c.M) continue;
-                const int64_t orow = (KIND == 1 && row_map) ? (int64_t)row_map[row_base + row] : (int64_t)row;
+                const int64_t orow = row_map ? (int64_t)row_map[row_base + row] : (int64_t)row;
 #pragma unroll
                 for (int ni = 0; ni < Cfg::NI; ++ni) {
                     const int col = c.n0 + ni * MB + acc_col(c.lane);
                     if (col >= c.N) continue;
-                    const float v = acc[mi][ni][j];
-                    const size_t idx = (size_t)orow * ldc + col;
-                    if (KIND == 1) {
-                        const __bf16 h = (__bf16)v;
-                        Cb[idx] = __builtin_bit_cast(uint16_t, h);
-                    } else {
-                        Cf[idx] = accumulate ? Cf[idx] + v : v;
-                    }
+                    const __bf16 h = (__bf16)acc[mi][ni][j];
+                    Cb[(size_t)orow * ldc + col] = __builtin_bit_cast(uint16_t, h);
                 }
             }
     }
 
+    // KIND 0 needs N and ldc to be multiples of 4 and C 16-byte aligned (checked by the launcher).
     template <class Cfg>
-    static constexpr int lds_bytes() { return 0; }
+    static constexpr int lds_bytes() { return KIND == 0 ? (Cfg::BM / 2) * (Cfg::BN * 4 + 16) : 0; }
 };
 typedef EpiStore<0> EpiStoreDW;
 typedef EpiStore<1> EpiStoreDH;
