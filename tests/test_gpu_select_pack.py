@@ -151,6 +151,23 @@ def test_batch_estimator_is_unbiased_over_sampled_masks(lib):
     assert abs(vals.mean() - float(g.double().mean())) < 5 * se
 
 
+def test_maximum_sizes(lib):
+    # the largest supported batch of prompts, and a long item stream through the packer
+    rng = np.random.default_rng(1)
+    Q, G = 16384, 16
+    r = (rng.random((Q, G)) < 0.5).astype(np.float32)
+    hist = np.round(rng.random(Q), 3).astype(np.float32)
+    up, uc = rng.random(Q, dtype=np.float32), rng.random((Q, G), dtype=np.float32)
+    for fixed in (False, True):
+        ref, _ = _cmp_select(lib, r, hist, up, uc, 0.5, 0.5, fixed=fixed)
+    n = 65536
+    pl = rng.integers(16, 512, size=n).astype(np.int32)
+    cl = rng.integers(16, 2048, size=n).astype(np.int32)
+    _cmp_pack(lib, pl, cl, ref["keep_comp"].reshape(-1)[:n], 8192, 32)
+    with pytest.raises(lib.DppoError):
+        lib.dppo_select(np.zeros((16385, 2), np.float32), None, None, None, 0.5, 0.5, device=DEV)
+
+
 def test_select_rejects_bad_arguments(lib):
     r = np.zeros((2, 2), dtype=np.float32)
     with pytest.raises(lib.DppoError):
