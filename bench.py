@@ -25,8 +25,6 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak
 # (workload, kernel, recompute); an entry is deleted when that kernel changes, until the counters
 # are taken again.
 MEASURED_TRAFFIC_BYTES = {
-    ("qwen3_4b", "logits_gemm", False): 2.0 * 21491441 * 1024 + 9730031 * 1024,
-    ("qwen3_4b", "dh_gemm", False): 2.0 * 32697271 * 1024 + 161168 * 1024,
     ("qwen3_4b", "dw_gemm", False): 2.0 * 25039334 * 1024 + 1519360 * 1024,
 }
 

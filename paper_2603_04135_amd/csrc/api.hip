@@ -73,6 +73,7 @@ struct WsPlan {
     size_t fixed_bytes, row_bytes; // bytes independent of / proportional to the chunk size
     // region offsets
     size_t o_wt, o_logp, o_ell, o_kl, o_clip, o_seq, o_sratio, o_hc, o_hct, o_part, o_zg, o_gt, o_y, o_zy, o_lse, o_c;
+    size_t o_bref, o_mx, o_scale, o_redo_list, o_redo_sum, o_redo_count;   // bf16 backward only
     size_t total;
 };
 
@@ -106,6 +107,13 @@ void layout(const dppo_head_shape& s, bool bwd, int32_t n_cp, WsPlan& p) {
     p.o_zy = take((size_t)n_cp * 4);
     p.o_lse = take((size_t)n_cp * 4);
     p.o_c = take((size_t)n_cp * 4);
+    const size_t per_tok = bwd && s.dtype == 1 ? (size_t)n_cp * 4 : 0;
+    p.o_bref = take(per_tok);
+    p.o_mx = take(per_tok);
+    p.o_scale = take(per_tok);
+    p.o_redo_list = take(per_tok);
+    p.o_redo_sum = take(per_tok);
+    p.o_redo_count = take(per_tok ? 4 : 0);
     p.total = off;
 }
 
@@ -154,26 +162,43 @@ struct Regions {
     template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(base + off); }
 };
 
-// Forward statistics of one chunk: Hc (and HcT), targets, log-probs, lse. Leaves the chunk's
-// logits in the workspace when keep_z is set (always for float32).
+// Forward statistics of one chunk: Hc, targets, log-probs, lse. With keep_z the chunk's logits
+// stay in the workspace for the backward pass: as float32 logits (float32 path, which also gets
+// HcT), or as bf16 exponentials against the per-token reference left in the bref region (bf16 path).
 int chunk_forward(const dppo_head_shape& s, const WsPlan& p, char* ws, const void* H, const void* W,
-                   const int32_t* ids, const int32_t* loss_pos, ChunkView cv, bool bwd, bool keep_z,
+                   const int32_t* ids, const int32_t* loss_pos, ChunkView cv, bool keep_z,
                    float* logp_all, float* lse_all, hipStream_t st) {
     void* Hc = ws + p.o_hc;
-    void* HcT = bwd ? ws + p.o_hct : nullptr;
     int32_t* y = reinterpret_cast<int32_t*>(ws + p.o_y);
     float* zy = reinterpret_cast<float*>(ws + p.o_zy);
     float* lse_c = reinterpret_cast<float*>(ws + p.o_lse);
-    launch_gather_rows(s.dtype, H, ids, loss_pos, s.T, s.D, s.V, cv, Hc, HcT, y, st);
-    if (s.dtype == 1) {
+    launch_gather_rows(s.dtype, H, ids, loss_pos, s.T, s.D, s.V, cv, Hc, keep_z && s.dtype == 0 ? ws + p.o_hct : nullptr,
+                       y, st);
+    if (s.dtype == 1 && keep_z) {
+        float2* part = reinterpret_cast<float2*>(ws + p.o_part);
+        float* bref = reinterpret_cast<float*>(ws + p.o_bref);
+        float* mx = reinterpret_cast<float*>(ws + p.o_mx);
+        int32_t* redo_count = reinterpret_cast<int32_t*>(ws + p.o_redo_count);
+        int32_t* redo_list = reinterpret_cast<int32_t*>(ws + p.o_redo_list);
+        float* redo_sum = reinterpret_cast<float*>(ws + p.o_redo_sum);
+        // reference of the stored exponentials = the target logit: lse - reference = -logp of a
+        // token that was sampled from (nearly) this policy, a few units in any sane batch
+        launch_target_logit(1, Hc, W, y, cv.n_cp, s.D, zy, bref, redo_count, st);
+        {
+            StageTimer tm(DPPO_STAGE_LOGITS_GEMM, st);
+            const int rc = launch_mfma_logits_exp(W, s.V, s.D, Hc, cv.n_cp, part, bref, ws + p.o_zg, p.Vp, p.Vp, st);
+            if (rc != DPPO_OK) return rc;
+        }
+        launch_combine_exp(part, p.n_tiles, zy, bref, cv, lse_c, logp_all, mx, redo_count, redo_list, redo_sum, st);
+        launch_exp_redo_rows(redo_count, redo_list, redo_sum, Hc, W, s.V, p.Vp, s.D, zy, mx, cv, ws + p.o_zg, p.Vp,
+                             bref, lse_c, logp_all, st);
+    } else if (s.dtype == 1) {
         float2* part = reinterpret_cast<float2*>(ws + p.o_part);
         {
             StageTimer tm(DPPO_STAGE_LOGITS_GEMM, st);
-            const int rc = launch_mfma_logits(W, s.V, s.D, Hc, cv.n_cp, part, keep_z ? ws + p.o_zg : nullptr, p.Vp,
-                                              p.Vp, st);
-            if (rc != DPPO_OK) return rc;
+            launch_mfma_logits(W, s.V, s.D, Hc, cv.n_cp, part, st);
         }
-        launch_target_logit(1, Hc, W, y, cv.n_cp, s.D, zy, st);
+        launch_target_logit(1, Hc, W, y, cv.n_cp, s.D, zy, nullptr, nullptr, st);
         launch_combine_logprob(part, p.n_tiles, zy, cv, lse_c, logp_all, lse_all, st);
     } else {
         StoreSpec out{ws + p.o_zg, p.Vp, 0, 0, nullptr, 0};
@@ -343,7 +368,7 @@ int dppo_token_logprob(const dppo_head_shape* shape, const void* H, const void* 
         cv.n0 = n0;
         cv.n_c = (int32_t)((s.N - n0) < p.n_cp ? (s.N - n0) : p.n_cp);
         cv.n_cp = round_up32(cv.n_c, CHUNK_ALIGN);
-        if (int rc = chunk_forward(s, p, w, H, W, ids, loss_pos, cv, false, false, logp, lse, st)) return rc;
+        if (int rc = chunk_forward(s, p, w, H, W, ids, loss_pos, cv, false, logp, lse, st)) return rc;
     }
     return check_launch("dppo_token_logprob");
 }
@@ -398,7 +423,7 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
             cv.n0 = n0;
             cv.n_c = (int32_t)((s.N - n0) < p.n_cp ? (s.N - n0) : p.n_cp);
             cv.n_cp = round_up32(cv.n_c, CHUNK_ALIGN);
-            if (int rc = chunk_forward(s, p, w, H, W, ids, loss_pos, cv, false, false, logp_all, nullptr, st)) return rc;
+            if (int rc = chunk_forward(s, p, w, H, W, ids, loss_pos, cv, false, logp_all, nullptr, st)) return rc;
         }
         launch_seq_ratio(loss_cu, S, logp_all, logp_old, seq_ratio, st);
     }
@@ -410,7 +435,7 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
         cv.n_c = (int32_t)((s.N - n0) < p.n_cp ? (s.N - n0) : p.n_cp);
         cv.n_cp = round_up32(cv.n_c, CHUNK_ALIGN);
         const bool recompute = lp->recompute_logits != 0;
-        if (int rc = chunk_forward(s, p, w, H, W, ids, loss_pos, cv, true, !recompute, logp_all, nullptr, st)) return rc;
+        if (int rc = chunk_forward(s, p, w, H, W, ids, loss_pos, cv, s.dtype == 0 || !recompute, logp_all, nullptr, st)) return rc;
 
         TokenLossArgs ta;
         ta.loss_cu = loss_cu; ta.S = S; ta.seq_adv = seq_adv; ta.seq_coef = seq_coef;
@@ -423,20 +448,30 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
 
         const int32_t* y = reinterpret_cast<const int32_t*>(w + p.o_y);
         const float* lse_c = reinterpret_cast<const float*>(w + p.o_lse);
+        // bf16: the chunk region holds either gradient entries (recompute) or exponentials whose
+        // row scale goes to the dH epilogue and into the HcT operand of dW; in the blocked layout it
+        // serves both GEMMs. float32: row-major G and its transposed copy GT.
         void* G = w + p.o_zg;
-        void* GT = w + p.o_gt;
-        if (recompute) {
+        const float* row_scale = nullptr;
+        if (s.dtype == 0) {
+            StageTimer tm(DPPO_STAGE_GRAD_LOGITS, st);
+            launch_grad_logits_f32(reinterpret_cast<float*>(G), reinterpret_cast<float*>(w + p.o_gt), s.V, p.Vp, y, lse_c,
+                                   ta.c_chunk, cv.n_cp, st);
+        } else if (recompute) {
             StageTimer tm(DPPO_STAGE_LOGITS_GEMM, st);
             const int rc2 = launch_mfma_logits_grad(W, s.V, s.D, w + p.o_hc, cv.n_cp, y, lse_c, ta.c_chunk, G, p.Vp,
                                                     p.Vp, st);
             if (rc2 != DPPO_OK) return rc2;
         } else {
             StageTimer tm(DPPO_STAGE_GRAD_LOGITS, st);
-            launch_grad_logits(s.dtype, G, GT, s.V, p.Vp, y, lse_c, ta.c_chunk, cv.n_cp, st);
+            float* scale = reinterpret_cast<float*>(w + p.o_scale);
+            launch_softmax_scale(y, reinterpret_cast<const float*>(w + p.o_zy), reinterpret_cast<const float*>(w + p.o_bref),
+                                 lse_c, ta.c_chunk, cv, G, p.Vp, scale, st);
+            row_scale = scale;
         }
+        if (s.dtype == 1) launch_scale_transpose_bf16(w + p.o_hc, row_scale, cv.n_cp, s.D, w + p.o_hct, st);
 
-        // dH rows of the chunk: G[n_c, Vp] * WT[D, Vp]^T, scattered to the loss rows of dH
-        // (bf16: G is in the blocked chunk layout and serves both GEMMs; float32: row-major G and GT)
+        // dH rows of the chunk: diag(row_scale) G[n_c, Vp] * WT[D, Vp]^T, scattered to the loss rows of dH
         StoreSpec oh;
         oh.out_bf16 = s.dtype == 1; oh.accumulate = 0; oh.ldc = s.D;
         if (loss_pos) { oh.C = dH; oh.row_map = loss_pos; oh.row_base = n0; }
@@ -448,7 +483,7 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
         if (s.dtype == 1) {
             {
                 StageTimer tm(DPPO_STAGE_DH_GEMM, st);
-                launch_mfma_dh(G, p.Vp, w + p.o_wt, cv.n_c, s.D, oh, st);
+                launch_mfma_dh(G, p.Vp, w + p.o_wt, cv.n_c, s.D, row_scale, oh, st);
             }
             {
                 StageTimer tm(DPPO_STAGE_DW_GEMM, st);
@@ -457,7 +492,7 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
         } else {
             launch_gemm_plain_f32(reinterpret_cast<const float*>(G), p.Vp, reinterpret_cast<const float*>(w + p.o_wt),
                                   p.Vp, cv.n_c, s.D, p.Vp, oh, st);
-            launch_gemm_plain_f32(reinterpret_cast<const float*>(GT), cv.n_cp,
+            launch_gemm_plain_f32(reinterpret_cast<const float*>(w + p.o_gt), cv.n_cp,
                                   reinterpret_cast<const float*>(w + p.o_hct), cv.n_cp, s.V, s.D, cv.n_cp, ow, st);
         }
         first = false;

@@ -50,12 +50,34 @@ void launch_gather_rows(int dtype, const void* H, const int32_t* ids, const int3
 // WT[D, Vp] = transpose of W[V, D], columns v >= V zero.
 void launch_transpose_w(int dtype, const void* W, int32_t V, int32_t D, int32_t Vp, void* WT,
                         hipStream_t st);
-// zy[n] = Hc[n] . W[y[n]] in fp32.
+// zy[n] = Hc[n] . W[y[n]] in fp32; also copied to bref[n] and *flag cleared where not NULL.
 void launch_target_logit(int dtype, const void* Hc, const void* W, const int32_t* y, int32_t n_cp,
-                         int32_t D, float* zy, hipStream_t st);
+                         int32_t D, float* zy, float* bref, int32_t* flag, hipStream_t st);
 // lse from per-tile partial (max, sumexp) pairs part[tile][n_cp]; logp = zy - lse.
 void launch_combine_logprob(const float2* part, int32_t n_tiles, const float* zy, ChunkView cv,
                             float* lse_chunk, float* logp_out, float* lse_out, hipStream_t st);
+// Statistics of the GEMM that stores exponentials against the per-token reference bref[n]:
+// part[tile][n] = (max z, sum exp(z - bref[n])); lse = bref + log(sum), logp = zy - lse, mx[n] = row
+// maximum. Tokens whose sum is out of the safe range are appended to redo_list (count in
+// *redo_count, cleared beforehand by launch_target_logit) instead.
+void launch_combine_exp(const float2* part, int32_t n_tiles, const float* zy, const float* bref, ChunkView cv,
+                        float* lse_chunk, float* logp_out, float* mx, int32_t* redo_count, int32_t* redo_list,
+                        float* redo_sum, hipStream_t st);
+// Redoes the listed tokens against their row maximum, with plain fp32 dot products: E rows,
+// lse, logp, and bref[n] = mx[n]. Costs one pass over W per 8 listed tokens; nothing when the list
+// is empty.
+void launch_exp_redo_rows(const int32_t* redo_count, const int32_t* redo_list, float* redo_sum, const void* Hc,
+                          const void* W, int32_t V, int32_t Vp, int32_t D, const float* zy, const float* mx,
+                          ChunkView cv, void* E, int64_t lde, float* bref, float* lse_chunk, float* logp_out,
+                          hipStream_t st);
+// scale[n] = -c[n] exp(bref[n] - lse[n]) (0 beyond n_c) and the target entry of the stored
+// exponentials E (blocked chunk, pitch lde) replaced by exp(zy - bref) - exp(lse - bref), so that
+// scale[n] E[n, v] = c[n] (1[v == y[n]] - softmax[n, v]).
+void launch_softmax_scale(const int32_t* y, const float* zy, const float* bref, const float* lse, const float* c,
+                          ChunkView cv, void* E, int64_t lde, float* scale, hipStream_t st);
+// HcT[D, n_cp] = transpose of diag(scale) Hc[n_cp, D] in bf16 (scale NULL = 1).
+void launch_scale_transpose_bf16(const void* Hc, const float* scale, int32_t n_cp, int32_t D, void* HcT,
+                                 hipStream_t st);
 // fp32 path: row statistics straight from stored logits Z[n_cp, ldz].
 void launch_row_stats_f32(const float* Z, int64_t ldz, int32_t V, const int32_t* y, ChunkView cv,
                           float* lse_chunk, float* logp_out, float* lse_out, hipStream_t st);
@@ -78,13 +100,10 @@ void launch_seq_ratio(const int32_t* loss_cu, int32_t S, const float* logp, cons
 void launch_token_norm_coef(int32_t Q, int32_t G, const int32_t* comp_len, const float* coef, float* coef_out,
                             hipStream_t st);
 
-// In place over the chunk's stored logits: G[n,v] = c[n] (1[v==y[n]] - exp(z - lse[n])) for
-// v < V, 0 for V <= v < Vp.
-// dtype 0: all float, row-major [n_cp, Vp], also written transposed to GT[Vp, n_cp].
-// dtype 1: Z is fp16 and G bf16, both in the blocked chunk layout of the MFMA GEMMs (64 x 256
-// element blocks, Vp a multiple of 256); GT is not used.
-void launch_grad_logits(int dtype, void* ZG, void* GT, int32_t V, int32_t Vp, const int32_t* y,
-                        const float* lse, const float* c, int32_t n_cp, hipStream_t st);
+// float32 path, in place over the chunk's stored logits: G[n,v] = c[n] (1[v==y[n]] - exp(z - lse[n]))
+// for v < V, 0 for V <= v < Vp; row-major [n_cp, Vp], also written transposed to GT[Vp, n_cp].
+void launch_grad_logits_f32(float* ZG, float* GT, int32_t V, int32_t Vp, const int32_t* y, const float* lse,
+                            const float* c, int32_t n_cp, hipStream_t st);
 
 struct SeqReduceArgs {
     const int32_t* loss_cu; int32_t S; int64_t N;
@@ -114,23 +133,27 @@ void launch_gemm_plain_f32(const float* A, int64_t lda, const float* B, int64_t 
 // to the next multiple of the tile size, so operands are padded scratch buffers or clamped.
 int mfma_setup();   // one-time kernel attribute setup, returns dppo status
 // Vocabulary GEMM: rows = vocabulary entries (A = W[V,D]), columns = tokens (B = Hc[n_cp,D]).
-// Writes per-(row tile, token) partial (max, sum exp) to part[tile*n_cp + n]; if Z16 != NULL also
-// stores the chunk's logits as fp16 to Z16, a [n_cp, ldz] matrix in the blocked chunk layout
-// (blocks of 64 tokens x 256 vocabulary entries, each contiguous; block (i, j) at element
-// i * 64 * ldz + j * 16384). ldz = Vp must then be a multiple of mfma_vocab_tile() (whole tiles
-// are stored). Returns a dppo status.
+// Writes per-(row tile, token) partial (max, sum exp(z - max)) to part[tile*n_cp + n].
 int32_t mfma_logits_row_tiles(int32_t V);
 int32_t mfma_vocab_tile();
-int launch_mfma_logits(const void* W, int32_t V, int32_t D, const void* Hc, int32_t n_cp,
-                        float2* part, void* Z16, int64_t ldz, int32_t Vp, hipStream_t st);
+void launch_mfma_logits(const void* W, int32_t V, int32_t D, const void* Hc, int32_t n_cp, float2* part,
+                        hipStream_t st);
+// Same GEMM; stores E[n, v] = exp(z[n, v] - bref[n]) as bf16 (0 for V <= v < Vp) to E, a [n_cp, lde]
+// matrix in the blocked chunk layout (blocks of 64 tokens x 256 vocabulary entries, each
+// contiguous; block (i, j) at element i * 64 * lde + j * 16384); lde = Vp must be a multiple of
+// mfma_vocab_tile() (whole tiles are stored). part[tile*n_cp + n] = (max z, sum exp(z - bref[n]))
+// over the tile's rows. Returns a dppo status.
+int launch_mfma_logits_exp(const void* W, int32_t V, int32_t D, const void* Hc, int32_t n_cp, float2* part,
+                           const float* bref, void* E, int64_t lde, int32_t Vp, hipStream_t st);
 // Same GEMM, but the epilogue turns logits straight into gradient entries
 // G[n,v] = c[n] (1[v==y[n]] - exp(z - lse[n])) written as bf16 to the blocked chunk G (pitch ldg = Vp).
 int launch_mfma_logits_grad(const void* W, int32_t V, int32_t D, const void* Hc, int32_t n_cp,
                             const int32_t* y, const float* lse, const float* c, void* G, int64_t ldg,
                             int32_t Vp, hipStream_t st);
-// dH rows of a chunk: C[n_c, D] = G[n_c, Vp] WT[D, Vp]^T with G in the blocked chunk layout (pitch Vp).
-void launch_mfma_dh(const void* G, int32_t Vp, const void* WT, int32_t n_c, int32_t D, const StoreSpec& out,
-                    hipStream_t st);
+// dH rows of a chunk: C[n_c, D] = diag(row_scale) G[n_c, Vp] WT[D, Vp]^T with G in the blocked chunk
+// layout (pitch Vp); row_scale may be NULL (= 1).
+void launch_mfma_dh(const void* G, int32_t Vp, const void* WT, int32_t n_c, int32_t D, const float* row_scale,
+                    const StoreSpec& out, hipStream_t st);
 // dW of a chunk: C[V, D] (+)= G^T HcT^T = sum_n G[n, v] HcT[d, n], G read k-major from the same blocks.
 void launch_mfma_dw(const void* G, int32_t Vp, const void* HcT, int32_t n_cp, int32_t V, int32_t D,
                     const StoreSpec& out, hipStream_t st);

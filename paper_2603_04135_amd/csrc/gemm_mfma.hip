@@ -39,8 +39,8 @@ int mfma_setup() {
     static int status = [] {
         hipError_t e = allow_lds<CfgBig, EpiStoreDW, A_BLK_KM>();
         if (e == hipSuccess) e = allow_lds<CfgBig, EpiStoreDH, A_BLK_ROWS>();
-        if (e == hipSuccess) e = allow_lds<CfgBig, EpiLogits<true>>();
-        if (e == hipSuccess) e = allow_lds<CfgBig, EpiLogits<false>>();
+        if (e == hipSuccess) e = allow_lds<CfgBig, EpiLogits>();
+        if (e == hipSuccess) e = allow_lds<CfgBig, EpiLogitsExp>();
         if (e == hipSuccess) e = allow_lds<CfgBig, EpiLogitsGrad>();
         if (e != hipSuccess) return fail(DPPO_ERR_DEVICE, "hipFuncSetAttribute(dynamic LDS): %s", hipGetErrorString(e));
         return (int)DPPO_OK;
@@ -51,19 +51,20 @@ int mfma_setup() {
 int32_t mfma_logits_row_tiles(int32_t V) { return (int32_t)ceil_div(V, CfgBig::BM); }
 int32_t mfma_vocab_tile() { return CfgBig::BM; }
 
-int launch_mfma_logits(const void* W, int32_t V, int32_t D, const void* Hc, int32_t n_cp, float2* part,
-                        void* Z16, int64_t ldz, int32_t Vp, hipStream_t st) {
-    if (Z16) {
-        // the epilogue stores whole tiles: the caller pads the row pitch to whole vocabulary tiles
-        if (Vp % CfgBig::BM != 0 || ldz != Vp || Vp < V)
-            return fail(DPPO_ERR_UNSUPPORTED, "logits buffer not padded to whole vocabulary tiles (Vp %d, pitch %lld)", Vp,
-                        (long long)ldz);
-        EpiLogits<true> e{part, n_cp, reinterpret_cast<_Float16*>(Z16), ldz, Vp};
-        launch<CfgBig>(W, D, Hc, D, V, n_cp, D, e, st);
-    } else {
-        EpiLogits<false> e{part, n_cp, nullptr, 0, 0};
-        launch<CfgBig>(W, D, Hc, D, V, n_cp, D, e, st);
-    }
+void launch_mfma_logits(const void* W, int32_t V, int32_t D, const void* Hc, int32_t n_cp, float2* part,
+                        hipStream_t st) {
+    EpiLogits e{part, n_cp};
+    launch<CfgBig>(W, D, Hc, D, V, n_cp, D, e, st);
+}
+
+int launch_mfma_logits_exp(const void* W, int32_t V, int32_t D, const void* Hc, int32_t n_cp, float2* part,
+                           const float* bref, void* E, int64_t lde, int32_t Vp, hipStream_t st) {
+    // the epilogue stores whole tiles: the caller pads the row pitch to whole vocabulary tiles
+    if (Vp % CfgBig::BM != 0 || lde != Vp || Vp < V)
+        return fail(DPPO_ERR_UNSUPPORTED, "chunk buffer not padded to whole vocabulary tiles (Vp %d, pitch %lld)", Vp,
+                    (long long)lde);
+    EpiLogitsExp e{part, n_cp, bref, reinterpret_cast<uint16_t*>(E), lde};
+    launch<CfgBig>(W, D, Hc, D, V, n_cp, D, e, st);
     return DPPO_OK;
 }
 
@@ -78,15 +79,15 @@ int launch_mfma_logits_grad(const void* W, int32_t V, int32_t D, const void* Hc,
     return DPPO_OK;
 }
 
-void launch_mfma_dh(const void* G, int32_t Vp, const void* WT, int32_t n_c, int32_t D, const StoreSpec& out,
-                    hipStream_t st) {
-    EpiStoreDH e{nullptr, reinterpret_cast<uint16_t*>(out.C), out.ldc, 0, out.row_map, out.row_base};
+void launch_mfma_dh(const void* G, int32_t Vp, const void* WT, int32_t n_c, int32_t D, const float* row_scale,
+                    const StoreSpec& out, hipStream_t st) {
+    EpiStoreDH e{nullptr, reinterpret_cast<uint16_t*>(out.C), out.ldc, 0, out.row_map, out.row_base, row_scale};
     launch<CfgBig, A_BLK_ROWS>(G, Vp, WT, Vp, n_c, D, Vp, e, st);
 }
 
 void launch_mfma_dw(const void* G, int32_t Vp, const void* HcT, int32_t n_cp, int32_t V, int32_t D,
                     const StoreSpec& out, hipStream_t st) {
-    EpiStoreDW e{reinterpret_cast<float*>(out.C), nullptr, out.ldc, out.accumulate, nullptr, 0};
+    EpiStoreDW e{reinterpret_cast<float*>(out.C), nullptr, out.ldc, out.accumulate, nullptr, 0, nullptr};
     launch<CfgBig, A_BLK_KM>(G, Vp, HcT, n_cp, V, D, n_cp, e, st);
 }
 

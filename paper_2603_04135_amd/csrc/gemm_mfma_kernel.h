@@ -2,7 +2,8 @@
 // and the epilogues of the LM-head path fused onto its accumulators:
 //   * vocabulary GEMM (rows = vocabulary entries, columns = tokens): running max / sum-exp per
 //     token over the tile's vocabulary rows, so full logits never reach HBM; optionally the
-//     chunk's logits as fp16, or directly the softmax-gradient entries in bf16;
+//     chunk's exponentials against a per-token reference, or directly the softmax-gradient
+//     entries, in bf16;
 //   * plain stores (fp32 / bf16, overwrite or accumulate, optional row scatter) for dH and dW.
 //
 // One workgroup owns a BM x BN output tile. K is streamed in slices of BK elements that go from
@@ -37,7 +38,6 @@ namespace mfma {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
@@ -387,6 +387,7 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
 template <int KIND>
 struct EpiStore {
     float* Cf; uint16_t* Cb; int64_t ldc; int accumulate; const int32_t* row_map; int64_t row_base;
+    const float* row_scale;   // KIND 1: output row m is multiplied by row_scale[m] if not NULL
 
     template <class Cfg>
     __device__ __forceinline__ void run(f32x4 (&acc)[Cfg::MI][Cfg::NI], const TileCtx& c) const {
@@ -435,11 +436,12 @@ struct EpiStore {
                 const int row = c.m0 + mi * MB + acc_row(c.lane, j);
                 if (row >= c.M) continue;
                 const int64_t orow = row_map ? (int64_t)row_map[row_base + row] : (int64_t)row;
+                const float rs = row_scale ? row_scale[row] : 1.0f;
 #pragma unroll
                 for (int ni = 0; ni < Cfg::NI; ++ni) {
                     const int col = c.n0 + ni * MB + acc_col(c.lane);
                     if (col >= c.N) continue;
-                    const __bf16 h = (__bf16)acc[mi][ni][j];
+                    const __bf16 h = (__bf16)(acc[mi][ni][j] * rs);
                     Cb[(size_t)orow * ldc + col] = __builtin_bit_cast(uint16_t, h);
                 }
             }
@@ -465,46 +467,21 @@ __device__ __forceinline__ void store_staged_row(const TileCtx& c, uint16_t* dst
     __builtin_nontemporal_store(val, reinterpret_cast<u32x4*>(dst + blk_offset(c.bn0 + r, c.bm0 + ch * 8, ld)));
 }
 
-// Rows = vocabulary entries, columns = tokens.
-template <bool STORE_Z>
+// Rows = vocabulary entries, columns = tokens: per-(row tile, token) running max and sum of
+// exponentials, nothing else leaves the tile.
 struct EpiLogits {
     float2* part; int64_t n_cp;    // part[tile_m * n_cp + token]
-    _Float16* Z16; int64_t ldz; int Vp;   // Z16: [n_cp, ldz] in BLK_R x BLK_C blocks (blk_offset)
 
     template <class Cfg>
     __device__ __forceinline__ void run(f32x4 (&acc)[Cfg::MI][Cfg::NI], const TileCtx& c) const {
         constexpr int MI = Cfg::MI, NI = Cfg::NI;
         const float NEG_INF = -__builtin_inff();
-        // LDS (free after the main loop's closing barrier): the tile's logits as fp16, laid out
-        // [token][vocabulary row] so that they leave as 16-byte stores that fill the tile's four
-        // 32 KB blocks of the chunk front to back, then the per-wavefront (max, sum) pairs of the
-        // WGM wavefronts that share a token.
-        constexpr int ZPITCH = Cfg::BM * 2 + 16;      // bytes per token row; +16 staggers the banks
-        float2* red = reinterpret_cast<float2*>(c.smem + (STORE_Z ? Cfg::BN * ZPITCH : 0));
-        if (STORE_Z) {
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni) {
-                const int tok = c.wave_n * Cfg::WTN + ni * MB + acc_col(c.lane);
-#pragma unroll
-                for (int mi = 0; mi < MI; ++mi) {
-                    const int vloc = c.wave_m * Cfg::WTM + mi * MB + acc_row(c.lane, 0);
-                    f16x4 h;
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        float z = acc[mi][ni][q];
-                        z = fminf(fmaxf(z, -65504.0f), 65504.0f);
-                        h[q] = (_Float16)z;
-                    }
-                    *reinterpret_cast<f16x4*>(c.smem + tok * ZPITCH + vloc * 2) = h;
-                }
-            }
-            __syncthreads();
-        }
+        float2* red = reinterpret_cast<float2*>(c.smem);   // (max, sum) pairs of the WGM wavefronts that share a token
         // running max over this wavefront's vocabulary rows, per token column: in-lane over the
-        // blocks, then across the four lane groups that hold the column's other rows
+        // blocks, then across the four lane groups that hold the column's other rows.
         // Only the last row of tiles has vocabulary rows beyond M; every other tile takes the
         // branch that is compiled without the row masks.
-        float mx[NI], mref[NI], sm[NI];
+        float mx[NI], sm[NI];
         auto reduce = [&](auto full_tag) __attribute__((always_inline)) {
             constexpr bool FULL = decltype(full_tag)::value;
 #pragma unroll
@@ -521,37 +498,17 @@ struct EpiLogits {
                 m = fmaxf(m, __shfl_xor(m, 16, 64));
                 m = fmaxf(m, __shfl_xor(m, 32, 64));
                 mx[ni] = m;
-                mref[ni] = (m == NEG_INF) ? 0.0f : m;
-                sm[ni] = 0.0f;
-            }
-            // The store path of a compute unit takes a 1 KB store instruction only every few dozen
-            // cycles, so the 16-byte stores of the staged tile (32 lanes x 16 bytes = one 512-byte token
-            // row piece, two rows per instruction) are interleaved with the exponentials of the sum:
-            // the arithmetic runs while the store queue drains.
-            constexpr int CH = Cfg::BM / 8;                     // 16-byte chunks per row
-            constexpr int ROWS_PER_PASS = Cfg::NT / CH;
-            constexpr int PASSES = Cfg::BN / ROWS_PER_PASS;
-            constexpr int TERMS = MI * NI * 4;                  // exponentials per lane
-            static_assert(TERMS % PASSES == 0, "terms per store pass");
-            constexpr int TPP = TERMS / PASSES;
-            const int ch = c.tid % CH;
-            // ldz is a multiple of BM = BLK_C (checked by the launcher), so every column of the tile has a
-            // home in Z16 and the stores need no branch, which would undo the interleaving.
-            static_assert(!STORE_Z || (Cfg::BM == BLK_C && Cfg::BN % BLK_R == 0), "tile = whole blocks");
+                const float mref = (m == NEG_INF) ? 0.0f : m;
+                float s = 0.0f;
 #pragma unroll
-            for (int it = 0; it < PASSES; ++it) {
-                if (STORE_Z)
-                    store_staged_row<Cfg>(c, reinterpret_cast<uint16_t*>(Z16), ldz, c.tid / CH + it * ROWS_PER_PASS, ch);
-                __builtin_amdgcn_sched_barrier(0);
+                for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-                for (int e = 0; e < TPP; ++e) {
-                    const int idx = it * TPP + e;
-                    const int ni = idx / (MI * 4), mi = (idx / 4) % MI, j = idx % 4;
-                    const int row = c.m0 + mi * MB + acc_row(c.lane, j);
-                    const float ex = __builtin_amdgcn_exp2f((acc[mi][ni][j] - mref[ni]) * LOG2E);
-                    sm[ni] += (FULL || row < c.M) ? ex : 0.0f;
-                }
-                __builtin_amdgcn_sched_barrier(0);
+                    for (int j = 0; j < 4; ++j) {
+                        const int row = c.m0 + mi * MB + acc_row(c.lane, j);
+                        const float ex = __builtin_amdgcn_exp2f((acc[mi][ni][j] - mref) * LOG2E);
+                        s += (FULL || row < c.M) ? ex : 0.0f;
+                    }
+                sm[ni] = s;
             }
         };
         if (c.bm0 + Cfg::BM <= c.M) reduce(std::true_type{});
@@ -583,9 +540,126 @@ struct EpiLogits {
     }
 
     template <class Cfg>
-    static constexpr int lds_bytes() {
-        return (STORE_Z ? Cfg::BN * (Cfg::BM * 2 + 16) : 0) + Cfg::WGM * Cfg::BN * 8;
+    static constexpr int lds_bytes() { return Cfg::WGM * Cfg::BN * 8; }
+};
+
+// Rows = vocabulary entries, columns = tokens. What the backward pass needs of the logits is the
+// softmax, and exp(z - lse) cannot be formed before the whole row has been seen; but bf16 has the
+// exponent range of fp32, so the tile stores E[n, v] = exp(z[n, v] - b[n]) against any per-token
+// reference b[n] that is within the exponent range of lse[n]. The softmax gradient is then a row
+// scaling of E, c[n] (1[v = y] - p[n, v]) = s[n] (E[n, v] - 1[v = y] exp(lse[n] - b[n])) with
+// s[n] = -c[n] exp(b[n] - lse[n]), which the two backward GEMMs apply on their small operands, and
+// the stored chunk is never read and rewritten by an elementwise pass. E goes to the blocked
+// chunk as bf16 (0 for the vocabulary padding). part[tile][token] = (max z, sum exp(z - b)) over
+// the tile's rows: the sums of all tiles share the reference and just add up; the max gives the
+// caller a safe reference for redoing the rows whose reference was too far off.
+struct EpiLogitsExp {
+    float2* part; int64_t n_cp;
+    const float* bref;
+    uint16_t* E; int64_t lde;      // [n_cp, lde] in BLK_R x BLK_C blocks (blk_offset)
+
+    template <class Cfg>
+    __device__ __forceinline__ void run(f32x4 (&acc)[Cfg::MI][Cfg::NI], const TileCtx& c) const {
+        constexpr int MI = Cfg::MI, NI = Cfg::NI;
+        static_assert(Cfg::BM == BLK_C && Cfg::BN % BLK_R == 0, "tile = whole blocks");
+        const float NEG_INF = -__builtin_inff();
+        // LDS (free after the main loop's closing barrier): the tile's E as bf16, laid out
+        // [token][vocabulary row] so that it leaves as 16-byte stores that fill the tile's four
+        // 32 KB blocks of the chunk, then the per-wavefront (max, sum) pairs.
+        constexpr int ZPITCH = Cfg::BM * 2 + 16;      // bytes per token row; +16 staggers the banks
+        float2* red = reinterpret_cast<float2*>(c.smem + Cfg::BN * ZPITCH);
+        float mx[NI], sm[NI], bl[NI];
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+            const int64_t col = c.bn0 + c.wave_n * Cfg::WTN + ni * MB + acc_col(c.lane);
+            bl[ni] = (col < n_cp ? bref[col] : 0.0f) * LOG2E;
+            mx[ni] = NEG_INF;
+            sm[ni] = 0.0f;
+        }
+        // The stores of a tile leave slowly (every compute unit reaches its epilogue at about the
+        // same time, and together they saturate the write path), so the work is cut into the NI
+        // token blocks of a wavefront column: while the 16-byte stores of block q - 1 drain (32 lanes
+        // x 16 bytes = one 512-byte token row piece, two rows per instruction), the exponentials of
+        // block q are computed and staged.
+        constexpr int CH = Cfg::BM / 8;                     // 16-byte chunks per row
+        constexpr int RPP = Cfg::NT / CH;                   // token rows per store pass
+        constexpr int PART_ROWS = Cfg::BN / NI;             // token rows of one part
+        constexpr int PASSES = PART_ROWS / RPP;             // store passes per part
+        static_assert(PART_ROWS % RPP == 0 && MI % PASSES == 0, "block rows per store pass");
+        constexpr int GPP = MI / PASSES;
+        const int ch = c.tid % CH;
+        auto body = [&](auto full_tag) __attribute__((always_inline)) {
+            constexpr bool FULL = decltype(full_tag)::value;
+            auto stage = [&](int ni, int mi) __attribute__((always_inline)) {
+                const int tok = c.wave_n * Cfg::WTN + ni * MB + acc_col(c.lane);
+                const int vloc = c.wave_m * Cfg::WTM + mi * MB + acc_row(c.lane, 0);
+                bf16x4 h;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float z = acc[mi][ni][q];
+                    const bool ok = FULL || (c.bm0 + vloc + q < c.M);
+                    float e = __builtin_amdgcn_exp2f(__builtin_fmaf(z, LOG2E, -bl[ni]));
+                    e = ok ? e : 0.0f;
+                    mx[ni] = fmaxf(mx[ni], ok ? z : NEG_INF);
+                    sm[ni] += e;
+                    const __bf16 b = (__bf16)e;   // scalar copy: reading h[q] back right after writing it miscompiles
+                    h[q] = b;
+                }
+                *reinterpret_cast<bf16x4*>(c.smem + tok * ZPITCH + vloc * 2) = h;
+            };
+            auto store_pass = [&](int part, int it) __attribute__((always_inline)) {
+                const int idx = it * RPP + c.tid / CH;                    // row among the part's rows
+                const int r = (idx / MB) * Cfg::WTN + part * MB + idx % MB;
+                store_staged_row<Cfg>(c, E, lde, r, ch);
+            };
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) stage(0, mi);
+            __syncthreads();
+#pragma unroll
+            for (int part = 1; part < NI; ++part) {
+#pragma unroll
+                for (int it = 0; it < PASSES; ++it) {
+                    store_pass(part - 1, it);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int e = 0; e < GPP; ++e) stage(part, it * GPP + e);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                __syncthreads();
+            }
+#pragma unroll
+            for (int it = 0; it < PASSES; ++it) store_pass(NI - 1, it);
+        };
+        if (c.bm0 + Cfg::BM <= c.M) body(std::true_type{});
+        else body(std::false_type{});
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+            mx[ni] = fmaxf(mx[ni], __shfl_xor(mx[ni], 16, 64));
+            mx[ni] = fmaxf(mx[ni], __shfl_xor(mx[ni], 32, 64));
+            sm[ni] += __shfl_xor(sm[ni], 16, 64);
+            sm[ni] += __shfl_xor(sm[ni], 32, 64);
+        }
+        if (c.lane < MB) {
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+                red[c.wave_m * Cfg::BN + c.wave_n * Cfg::WTN + ni * MB + c.lane] = make_float2(mx[ni], sm[ni]);
+        }
+        __syncthreads();
+        for (int t = c.tid; t < Cfg::BN; t += Cfg::NT) {
+            float m = NEG_INF, s = 0.0f;
+#pragma unroll
+            for (int w = 0; w < Cfg::WGM; ++w) {
+                const float2 r = red[w * Cfg::BN + t];
+                m = fmaxf(m, r.x);
+                s += r.y;
+            }
+            const int64_t tok = c.bn0 + t;
+            if (tok < n_cp) part[(int64_t)c.tm * n_cp + tok] = make_float2(m, s);
+        }
     }
+
+    template <class Cfg>
+    static constexpr int lds_bytes() { return Cfg::BN * (Cfg::BM * 2 + 16) + Cfg::WGM * Cfg::BN * 8; }
 };
 
 // Rows = vocabulary entries, columns = tokens: softmax-gradient entries straight from the logits,

@@ -1,7 +1,8 @@
 // HBM-bound kernels around the vocabulary GEMMs of the LM-head path: row gather and
 // transposes, target logits, combination of per-tile softmax partials, the per-token
-// surrogate + KL terms of Eq. 1 and their derivative, the softmax-gradient pass over a stored
-// logits chunk, and the segmented (per packed sequence) loss reduction.
+// surrogate + KL terms of Eq. 1 and their derivative, the row scales that turn a chunk of stored
+// exponentials into softmax gradients (bf16 path) or the softmax-gradient pass over a stored logits
+// chunk (float32 path), and the segmented (per packed sequence) loss reduction.
 // All global accesses are coalesced 16-byte (or full-wave contiguous) transactions; the
 // transposes go through padded LDS tiles.
 #include "dppo_internal.h"
@@ -9,8 +10,6 @@
 namespace dppo {
 namespace {
 
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t x) { return __uint_as_float((uint32_t)x << 16); }
@@ -72,20 +71,26 @@ __global__ void targets_kernel(const int32_t* __restrict__ ids, const int32_t* _
 }
 
 // ------------------------------------------------------------------------------------
-// One wavefront per token: zy[n] = Hc[n] . W[y[n]]
+// One wavefront per token: zy[n] = Hc[n] . W[y[n]], copied to bref[n] if bref is not NULL;
+// clears *flag if flag is not NULL.
 template <typename E>
 __global__ __launch_bounds__(256) void target_logit_kernel(const E* __restrict__ Hc, const E* __restrict__ W,
                                                            const int32_t* __restrict__ y, int32_t n_cp, int32_t D,
-                                                           float* __restrict__ zy) {
+                                                           float* __restrict__ zy, float* __restrict__ bref,
+                                                           int32_t* __restrict__ flag) {
     const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
+    if (flag && blockIdx.x == 0 && threadIdx.x == 0) *flag = 0;
     if (n >= n_cp) return;
     const E* h = Hc + (size_t)n * D;
     const E* w = W + (size_t)y[n] * D;
     float s = 0.0f;
     for (int d = lane; d < D; d += 64) s = fmaf(to_f32(h[d]), to_f32(w[d]), s);
     for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-    if (lane == 0) zy[n] = s;
+    if (lane == 0) {
+        zy[n] = s;
+        if (bref) bref[n] = s;
+    }
 }
 
 // ------------------------------------------------------------------------------------
@@ -125,6 +130,160 @@ __global__ __launch_bounds__(256) void combine_logprob_kernel(const float2* __re
     lse_chunk[n] = lse;
     logp_out[n0 + n] = zy[n] - lse;
     if (lse_out) lse_out[n0 + n] = lse;
+}
+
+// Same split of the work for the GEMM that stores exponentials: part[tile][n] = (max z, sum of
+// exp(z - bref[n])) with one reference per token, so the sums of the tiles add up and
+// lse = bref + log(sum). A sum so large that the stored exponentials, or the sums the backward
+// GEMMs form of them, could leave the float range (reference = target logit: a target token with
+// log-prob below about -69) puts the token on the redo list instead.
+constexpr float EXP_SUM_LIMIT = 1e30f;
+__global__ __launch_bounds__(256) void combine_exp_kernel(const float2* __restrict__ part, int32_t n_tiles,
+                                                          const float* __restrict__ zy,
+                                                          const float* __restrict__ bref, int64_t n0, int32_t n_c,
+                                                          int32_t n_cp, float* __restrict__ lse_chunk,
+                                                          float* __restrict__ logp_out, float* __restrict__ mx,
+                                                          int32_t* redo_count, int32_t* __restrict__ redo_list,
+                                                          float* __restrict__ redo_sum) {
+    __shared__ float2 red[4][64];
+    const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int n = blockIdx.x * 64 + lane;
+    float m = -__builtin_inff(), s = 0.0f;
+    if (n < n_cp) {
+        for (int t = q; t < n_tiles; t += 4) {
+            const float2 p = part[(size_t)t * n_cp + n];
+            m = fmaxf(m, p.x);
+            s += p.y;
+        }
+    }
+    red[q][lane] = make_float2(m, s);
+    __syncthreads();
+    if (q != 0 || n >= n_cp) return;
+#pragma unroll
+    for (int i = 1; i < 4; ++i) {
+        m = fmaxf(m, red[i][lane].x);
+        s += red[i][lane].y;
+    }
+    mx[n] = m;
+    if (n >= n_c) { lse_chunk[n] = 0.0f; return; }
+    if (!(s < EXP_SUM_LIMIT)) {
+        redo_list[atomicAdd(redo_count, 1)] = n;
+        redo_sum[n] = 0.0f;
+        return;
+    }
+    const float lse = bref[n] + logf(s);
+    lse_chunk[n] = lse;
+    logp_out[n0 + n] = zy[n] - lse;
+}
+
+// Slow exact path for the tokens on the redo list: E[n, v] = exp(Hc[n] . W[v] - mx[n]) with fp32
+// dot products, 8 listed tokens x 256 vocabulary entries per workgroup pass (one thread per
+// vocabulary entry, the token rows in LDS in slabs of REDO_SLAB columns), row sums by atomic adds.
+constexpr int REDO_TOK = 8, REDO_SLAB = 2048;
+__global__ __launch_bounds__(256) void exp_redo_rows_kernel(const int32_t* redo_count,
+                                                            const int32_t* __restrict__ redo_list,
+                                                            const uint16_t* __restrict__ Hc,
+                                                            const uint16_t* __restrict__ W, int32_t V, int32_t D,
+                                                            const float* __restrict__ mx, uint16_t* __restrict__ E,
+                                                            int64_t lde, float* redo_sum) {
+    __shared__ uint4 hs[REDO_TOK][REDO_SLAB / 8];
+    const int cnt = *reinterpret_cast<const volatile int32_t*>(redo_count);
+    const int v = blockIdx.x * 256 + threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int vr = v < V ? v : V - 1;
+    for (int g = blockIdx.y; g * REDO_TOK < cnt; g += gridDim.y) {
+        const int nt = (cnt - g * REDO_TOK) < REDO_TOK ? (cnt - g * REDO_TOK) : REDO_TOK;
+        float acc[REDO_TOK];
+#pragma unroll
+        for (int t = 0; t < REDO_TOK; ++t) acc[t] = 0.0f;
+        for (int d0 = 0; d0 < D; d0 += REDO_SLAB) {
+            const int dw = ((D - d0) < REDO_SLAB ? (D - d0) : REDO_SLAB) / 8;   // 16-byte pieces of the slab
+            __syncthreads();
+            for (int i = threadIdx.x; i < REDO_TOK * dw; i += 256) {
+                const int t = i / dw, c = i % dw;
+                uint4 x = make_uint4(0, 0, 0, 0);
+                if (t < nt) x = *reinterpret_cast<const uint4*>(Hc + (size_t)redo_list[g * REDO_TOK + t] * D + d0 + c * 8);
+                hs[t][c] = x;
+            }
+            __syncthreads();
+            const uint4* wr = reinterpret_cast<const uint4*>(W + (size_t)vr * D + d0);
+            for (int c = 0; c < dw; ++c) {
+                const uint4 w8 = wr[c];
+                const uint32_t ww[4] = {w8.x, w8.y, w8.z, w8.w};
+#pragma unroll
+                for (int t = 0; t < REDO_TOK; ++t) {
+                    const uint4 h8 = hs[t][c];
+                    const uint32_t hh[4] = {h8.x, h8.y, h8.z, h8.w};
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        acc[t] = fmaf(__uint_as_float(ww[k] << 16), __uint_as_float(hh[k] << 16), acc[t]);
+                        acc[t] = fmaf(__uint_as_float(ww[k] & 0xffff0000u), __uint_as_float(hh[k] & 0xffff0000u), acc[t]);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < REDO_TOK; ++t) {
+            if (t >= nt) break;                                  // uniform over the workgroup
+            const int64_t n = redo_list[g * REDO_TOK + t];
+            float e = v < V ? expf(acc[t] - mx[n]) : 0.0f;
+            const __bf16 eb = (__bf16)e;
+            constexpr int64_t BR = 64, BC = 256;                 // blocked chunk layout; v < lde by the grid
+            E[(size_t)(n / BR) * BR * lde + (size_t)(v / BC) * (BR * BC) + (n % BR) * BC + v % BC] =
+                __builtin_bit_cast(uint16_t, eb);
+            for (int off = 32; off > 0; off >>= 1) e += __shfl_xor(e, off, 64);
+            if (lane == 0) atomicAdd(redo_sum + n, e);
+        }
+    }
+}
+
+__global__ void exp_redo_finish_kernel(const int32_t* redo_count, const int32_t* __restrict__ redo_list,
+                                       const float* __restrict__ redo_sum, const float* __restrict__ zy,
+                                       const float* __restrict__ mx, int64_t n0, float* __restrict__ bref,
+                                       float* __restrict__ lse_chunk, float* __restrict__ logp_out) {
+    const int cnt = *reinterpret_cast<const volatile int32_t*>(redo_count);
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < cnt; i += gridDim.x * blockDim.x) {
+        const int n = redo_list[i];
+        const float lse = mx[n] + logf(redo_sum[n]);
+        bref[n] = mx[n];
+        lse_chunk[n] = lse;
+        logp_out[n0 + n] = zy[n] - lse;
+    }
+}
+
+// Row scale of the stored exponentials and their entry at the target: with E[n, v] = exp(z - b[n]),
+// c[n] (1[v = y] - p[n, v]) = s[n] E'[n, v] for s[n] = -c[n] exp(b[n] - lse[n]) and E' = E except
+// E'[n, y[n]] = exp(zy[n] - b[n]) - exp(lse[n] - b[n]). Rows beyond n_c get s = 0.
+__global__ void softmax_scale_kernel(const int32_t* __restrict__ y, const float* __restrict__ zy,
+                                     const float* __restrict__ bref, const float* __restrict__ lse,
+                                     const float* __restrict__ cvec, int32_t n_c, int32_t n_cp,
+                                     uint16_t* __restrict__ E, int64_t lde, float* __restrict__ scale) {
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= n_cp) return;
+    if (n >= n_c) { scale[n] = 0.0f; return; }
+    const float b = bref[n], l = lse[n];
+    scale[n] = -cvec[n] * expf(b - l);
+    const __bf16 e = (__bf16)(expf(zy[n] - b) - expf(l - b));
+    const int64_t v = y[n];
+    constexpr int64_t BR = 64, BC = 256;   // blocked chunk layout
+    E[(size_t)(n / BR) * BR * lde + (size_t)(v / BC) * (BR * BC) + (n % BR) * BC + v % BC] =
+        __builtin_bit_cast(uint16_t, e);
+}
+
+// dstT[c, r] = bf16(scale[r] * src[r, c]) for a bf16 [n_rows, n_cols] matrix (both multiples of 64).
+__global__ __launch_bounds__(256) void scale_transpose_kernel(const uint16_t* __restrict__ src, int64_t ld_src,
+                                                              const float* __restrict__ scale,
+                                                              uint16_t* __restrict__ dstT, int64_t ld_dstT) {
+    __shared__ uint16_t tile[64][65];
+    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int rr = ty; rr < 64; rr += 4) {
+        const float sc = scale ? scale[r0 + rr] : 1.0f;
+        const __bf16 v = (__bf16)(sc * bf16_to_f32(src[(int64_t)(r0 + rr) * ld_src + c0 + tx]));
+        tile[rr][tx] = __builtin_bit_cast(uint16_t, v);
+    }
+    __syncthreads();
+    for (int cc = ty; cc < 64; cc += 4) dstT[(int64_t)(c0 + cc) * ld_dstT + r0 + tx] = tile[tx][cc];
 }
 
 // fp32 path: one workgroup per token over the stored logits row.
@@ -236,41 +395,6 @@ __global__ __launch_bounds__(256) void grad_logits_kernel(void* ZG, GT_* __restr
 #pragma unroll
         for (int q = 0; q < 8; ++q) g[q] = tile[v][kc * 8 + q];
         *reinterpret_cast<GV*>(GTp + (size_t)(v0 + v) * n_cp + nb + kc * 8) = g;
-    }
-}
-
-// Softmax-gradient pass over a stored bf16-path logits chunk in the blocked layout (blocks of
-// 64 tokens x 256 vocabulary entries, each a contiguous 32 KB run): fp16 logits become bf16
-// gradient entries in place. One workgroup per block; every access is a contiguous 16-byte vector.
-// No transposed copy: the dW GEMM reads the same blocks k-major.
-__global__ __launch_bounds__(256) void grad_logits_blocked_kernel(void* ZG, int32_t V, int64_t ld,
-                                                                  const int32_t* __restrict__ y,
-                                                                  const float* __restrict__ lse,
-                                                                  const float* __restrict__ cvec) {
-    constexpr int BR = 64, BC = 256;
-    const int v_blk = blockIdx.x, n_blk = blockIdx.y;
-    char* base = reinterpret_cast<char*>(ZG) + ((size_t)n_blk * BR * ld + (size_t)v_blk * (BR * BC)) * 2;
-    const int t = threadIdx.x;
-    const int cc = t & 31;               // 16-byte chunk inside a 512-byte block row
-#pragma unroll
-    for (int pass = 0; pass < BR / 8; ++pass) {
-        const int r = (t >> 5) + pass * 8;
-        const int64_t n = (int64_t)n_blk * BR + r;
-        const float l = lse[n], cn = cvec[n];
-        const int yt = y[n];
-        char* p = base + (r * BC + cc * 8) * 2;
-        const f16x8 z = __builtin_nontemporal_load(reinterpret_cast<const f16x8*>(p));   // read once
-        bf16x8 g;
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            const int v = v_blk * BC + cc * 8 + q;
-            const float pr = expf((float)z[q] - l);
-            float gv = cn * ((v == yt ? 1.0f : 0.0f) - pr);
-            gv = v < V ? gv : 0.0f;
-            const __bf16 b = (__bf16)gv;   // keep the scalar: reading g[q] back right after writing it miscompiles
-            g[q] = b;
-        }
-        __builtin_nontemporal_store(g, reinterpret_cast<bf16x8*>(p));
     }
 }
 
@@ -408,14 +532,49 @@ void launch_transpose_w(int dtype, const void* W, int32_t V, int32_t D, int32_t 
 }
 
 void launch_target_logit(int dtype, const void* Hc, const void* W, const int32_t* y, int32_t n_cp, int32_t D,
-                         float* zy, hipStream_t st) {
+                         float* zy, float* bref, int32_t* flag, hipStream_t st) {
     const unsigned blocks = (unsigned)ceil_div(n_cp, 4);
     if (dtype == 1)
         target_logit_kernel<uint16_t><<<blocks, 256, 0, st>>>(reinterpret_cast<const uint16_t*>(Hc),
-                                                              reinterpret_cast<const uint16_t*>(W), y, n_cp, D, zy);
+                                                              reinterpret_cast<const uint16_t*>(W), y, n_cp, D, zy,
+                                                              bref, flag);
     else
         target_logit_kernel<float><<<blocks, 256, 0, st>>>(reinterpret_cast<const float*>(Hc),
-                                                           reinterpret_cast<const float*>(W), y, n_cp, D, zy);
+                                                           reinterpret_cast<const float*>(W), y, n_cp, D, zy, bref,
+                                                           flag);
+}
+
+void launch_combine_exp(const float2* part, int32_t n_tiles, const float* zy, const float* bref, ChunkView cv,
+                        float* lse_chunk, float* logp_out, float* mx, int32_t* redo_count, int32_t* redo_list,
+                        float* redo_sum, hipStream_t st) {
+    combine_exp_kernel<<<(unsigned)ceil_div(cv.n_cp, 64), 256, 0, st>>>(part, n_tiles, zy, bref, cv.n0, cv.n_c, cv.n_cp,
+                                                                        lse_chunk, logp_out, mx, redo_count, redo_list,
+                                                                        redo_sum);
+}
+
+void launch_exp_redo_rows(const int32_t* redo_count, const int32_t* redo_list, float* redo_sum, const void* Hc,
+                          const void* W, int32_t V, int32_t Vp, int32_t D, const float* zy, const float* mx,
+                          ChunkView cv, void* E, int64_t lde, float* bref, float* lse_chunk, float* logp_out,
+                          hipStream_t st) {
+    dim3 grid((unsigned)(Vp / 256), 4);
+    exp_redo_rows_kernel<<<grid, 256, 0, st>>>(redo_count, redo_list, reinterpret_cast<const uint16_t*>(Hc),
+                                               reinterpret_cast<const uint16_t*>(W), V, D, mx,
+                                               reinterpret_cast<uint16_t*>(E), lde, redo_sum);
+    exp_redo_finish_kernel<<<4, 256, 0, st>>>(redo_count, redo_list, redo_sum, zy, mx, cv.n0, bref, lse_chunk,
+                                              logp_out);
+}
+
+void launch_softmax_scale(const int32_t* y, const float* zy, const float* bref, const float* lse, const float* c,
+                          ChunkView cv, void* E, int64_t lde, float* scale, hipStream_t st) {
+    softmax_scale_kernel<<<(unsigned)ceil_div(cv.n_cp, 256), 256, 0, st>>>(y, zy, bref, lse, c, cv.n_c, cv.n_cp,
+                                                                           reinterpret_cast<uint16_t*>(E), lde, scale);
+}
+
+void launch_scale_transpose_bf16(const void* Hc, const float* scale, int32_t n_cp, int32_t D, void* HcT,
+                                 hipStream_t st) {
+    dim3 grid((unsigned)(D / 64), (unsigned)(n_cp / 64));
+    scale_transpose_kernel<<<grid, 256, 0, st>>>(reinterpret_cast<const uint16_t*>(Hc), D, scale,
+                                                 reinterpret_cast<uint16_t*>(HcT), n_cp);
 }
 
 void launch_combine_logprob(const float2* part, int32_t n_tiles, const float* zy, ChunkView cv, float* lse_chunk,
@@ -445,16 +604,10 @@ void launch_token_norm_coef(int32_t Q, int32_t G, const int32_t* comp_len, const
     token_norm_coef_kernel<<<(unsigned)ceil_div(Q, 64), 64, 0, st>>>(Q, G, comp_len, coef, coef_out);
 }
 
-void launch_grad_logits(int dtype, void* ZG, void* GT, int32_t V, int32_t Vp, const int32_t* y, const float* lse,
-                        const float* c, int32_t n_cp, hipStream_t st) {
-    if (dtype == 1) {
-        dim3 grid((unsigned)(Vp / 256), (unsigned)(n_cp / 64));
-        grad_logits_blocked_kernel<<<grid, 256, 0, st>>>(ZG, V, Vp, y, lse, c);
-    } else {
-        dim3 grid((unsigned)(Vp / 64), (unsigned)(n_cp / 64));
-        grad_logits_kernel<float, float, f32x8, f32x8><<<grid, 256, 0, st>>>(ZG, reinterpret_cast<float*>(GT), V, Vp,
-                                                                             y, lse, c, n_cp);
-    }
+void launch_grad_logits_f32(float* ZG, float* GT, int32_t V, int32_t Vp, const int32_t* y, const float* lse,
+                            const float* c, int32_t n_cp, hipStream_t st) {
+    dim3 grid((unsigned)(Vp / 64), (unsigned)(n_cp / 64));
+    grad_logits_kernel<float, float, f32x8, f32x8><<<grid, 256, 0, st>>>(ZG, GT, V, Vp, y, lse, c, n_cp);
 }
 
 void launch_seq_reduce(const SeqReduceArgs& a, hipStream_t st) {
