@@ -73,7 +73,7 @@ struct WsPlan {
     size_t fixed_bytes, row_bytes; // bytes independent of / proportional to the chunk size
     // region offsets
     size_t o_wt, o_logp, o_ell, o_kl, o_clip, o_seq, o_sratio, o_hc, o_hct, o_part, o_zg, o_gt, o_y, o_zy, o_lse, o_c;
-    size_t o_bref, o_mx, o_scale, o_redo_list, o_redo_sum, o_redo_count;   // bf16 backward only
+    size_t o_bref, o_mx, o_scale, o_redo_list, o_redo_sum, o_redo_count, o_dwpart;   // bf16 backward only
     size_t total;
 };
 
@@ -97,6 +97,7 @@ void layout(const dppo_head_shape& s, bool bwd, int32_t n_cp, WsPlan& p) {
     p.o_clip = take(bwd ? N * 4 : 0);
     p.o_seq = take(bwd ? 3 * N * 4 : 0);
     p.o_sratio = take(bwd ? N * 4 : 0);
+    p.o_dwpart = take(bwd && s.dtype == 1 ? mfma_dw_partial_bytes() : 0);
     p.fixed_bytes = off;
     p.o_hc = take((size_t)n_cp * s.D * p.es);
     p.o_hct = take(bwd ? (size_t)n_cp * s.D * p.es : 0);
@@ -487,7 +488,7 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
             }
             {
                 StageTimer tm(DPPO_STAGE_DW_GEMM, st);
-                launch_mfma_dw(G, p.Vp, w + p.o_hct, cv.n_cp, s.V, s.D, ow, st);
+                launch_mfma_dw(G, p.Vp, w + p.o_hct, cv.n_cp, s.V, s.D, ow, reinterpret_cast<float*>(w + p.o_dwpart), st);
             }
         } else {
             launch_gemm_plain_f32(reinterpret_cast<const float*>(G), p.Vp, reinterpret_cast<const float*>(w + p.o_wt),

@@ -155,7 +155,10 @@ int launch_mfma_logits_grad(const void* W, int32_t V, int32_t D, const void* Hc,
 void launch_mfma_dh(const void* G, int32_t Vp, const void* WT, int32_t n_c, int32_t D, const float* row_scale,
                     const StoreSpec& out, hipStream_t st);
 // dW of a chunk: C[V, D] (+)= G^T HcT^T = sum_n G[n, v] HcT[d, n], G read k-major from the same blocks.
+// `partial` is scratch of mfma_dw_partial_bytes() bytes (or NULL): with it, the tiles of a
+// sparsely filled last round are split along K over the idle compute units.
+size_t mfma_dw_partial_bytes();
 void launch_mfma_dw(const void* G, int32_t Vp, const void* HcT, int32_t n_cp, int32_t V, int32_t D,
-                    const StoreSpec& out, hipStream_t st);
+                    const StoreSpec& out, float* partial, hipStream_t st);
 
 }  // namespace dppo

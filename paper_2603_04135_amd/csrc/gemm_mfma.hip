@@ -18,13 +18,41 @@ constexpr int lds_request() {
     return Cfg::LDS_BYTES > e ? Cfg::LDS_BYTES : e;
 }
 
+// Launches the tiles [tile0, tile0 + n_tiles) of the tile walk, each cut into k_parts work items
+// along K; n_tiles < 0: all tiles.
 template <class Cfg, int AM = A_ROWS, class Epi>
 void launch(const void* A, int64_t lda, const void* B, int64_t ldb, int M, int N, int K, const Epi& epi,
-            hipStream_t st) {
+            hipStream_t st, int tile0 = 0, int n_tiles = -1, int k_parts = 1) {
     const int tiles_m = (int)ceil_div(M, Cfg::BM), tiles_n = (int)ceil_div(N, Cfg::BN);
-    gemm_nt_kernel<Cfg, Epi, AM><<<dim3(tiles_m * tiles_n), dim3(Cfg::NT), lds_request<Cfg, Epi>(), st>>>(
+    if (n_tiles < 0) n_tiles = tiles_m * tiles_n - tile0;
+    if (n_tiles <= 0) return;
+    gemm_nt_kernel<Cfg, Epi, AM><<<dim3(n_tiles * k_parts), dim3(Cfg::NT), lds_request<Cfg, Epi>(), st>>>(
         reinterpret_cast<const uint16_t*>(A), lda, reinterpret_cast<const uint16_t*>(B), ldb, M, N, K, tiles_m,
-        tiles_n, epi);
+        tiles_n, tile0, k_parts, epi);
+}
+
+// Sums the k_parts partial tiles of each of the n_tiles tiles from tile0 on, in part order, into
+// C (overwrite or accumulate). One workgroup per 16 rows of a tile; N and ldc multiples of 4.
+template <class Cfg>
+__global__ __launch_bounds__(256) void sum_partial_tiles_kernel(const float* __restrict__ partial, int tile0,
+                                                                int k_parts, int tiles_m, int tiles_n, float* C,
+                                                                int64_t ldc, int M, int N, int accumulate) {
+    typedef float f32x4v __attribute__((ext_vector_type(4)));
+    constexpr int VPR = Cfg::BN / 4;
+    int tm, tn;
+    tile_coords<Cfg::GROUP_M>(tile0 + blockIdx.x, tiles_m, tiles_n, tm, tn);
+    const float* src = partial + (size_t)blockIdx.x * k_parts * (Cfg::BM * Cfg::BN);
+    for (int i = threadIdx.x; i < 16 * VPR; i += 256) {
+        const int r = blockIdx.y * 16 + i / VPR, cv = i % VPR;
+        const int row = tm * Cfg::BM + r, col = tn * Cfg::BN + cv * 4;
+        if (row >= M || col >= N) continue;
+        f32x4v v = *reinterpret_cast<const f32x4v*>(src + (size_t)r * Cfg::BN + cv * 4);
+        for (int p = 1; p < k_parts; ++p)
+            v += *reinterpret_cast<const f32x4v*>(src + (size_t)p * (Cfg::BM * Cfg::BN) + (size_t)r * Cfg::BN + cv * 4);
+        f32x4v* dst = reinterpret_cast<f32x4v*>(C + (size_t)row * ldc + col);
+        if (accumulate) v += *dst;
+        *dst = v;
+    }
 }
 
 template <class Cfg, class Epi, int AM = A_ROWS>
@@ -35,9 +63,14 @@ hipError_t allow_lds() {
 
 }  // namespace
 
+int g_compute_units = 0;   // of the device the setup ran on
+
 int mfma_setup() {
     static int status = [] {
-        hipError_t e = allow_lds<CfgBig, EpiStoreDW, A_BLK_KM>();
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&g_compute_units, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess) e = allow_lds<CfgBig, EpiStoreDW, A_BLK_KM>();
         if (e == hipSuccess) e = allow_lds<CfgBig, EpiStoreDH, A_BLK_ROWS>();
         if (e == hipSuccess) e = allow_lds<CfgBig, EpiLogits>();
         if (e == hipSuccess) e = allow_lds<CfgBig, EpiLogitsExp>();
@@ -81,14 +114,40 @@ int launch_mfma_logits_grad(const void* W, int32_t V, int32_t D, const void* Hc,
 
 void launch_mfma_dh(const void* G, int32_t Vp, const void* WT, int32_t n_c, int32_t D, const float* row_scale,
                     const StoreSpec& out, hipStream_t st) {
-    EpiStoreDH e{nullptr, reinterpret_cast<uint16_t*>(out.C), out.ldc, 0, out.row_map, out.row_base, row_scale};
+    EpiStoreDH e{nullptr, reinterpret_cast<uint16_t*>(out.C), out.ldc, 0, out.row_map, out.row_base, row_scale, nullptr};
     launch<CfgBig, A_BLK_ROWS>(G, Vp, WT, Vp, n_c, D, Vp, e, st);
 }
 
+size_t mfma_dw_partial_bytes() { return (size_t)256 * CfgBig::BM * CfgBig::BN * 4; }
+
 void launch_mfma_dw(const void* G, int32_t Vp, const void* HcT, int32_t n_cp, int32_t V, int32_t D,
-                    const StoreSpec& out, hipStream_t st) {
-    EpiStoreDW e{reinterpret_cast<float*>(out.C), nullptr, out.ldc, out.accumulate, nullptr, 0, nullptr};
-    launch<CfgBig, A_BLK_KM>(G, Vp, HcT, n_cp, V, D, n_cp, e, st);
+                    const StoreSpec& out, float* partial, hipStream_t st) {
+    EpiStoreDW e{reinterpret_cast<float*>(out.C), nullptr, out.ldc, out.accumulate, nullptr, 0, nullptr, nullptr};
+    const int tiles_m = (int)ceil_div(V, CfgBig::BM), tiles_n = (int)ceil_div(D, CfgBig::BN);
+    const int tiles = tiles_m * tiles_n, cus = g_compute_units;
+    // One workgroup per compute unit at a time: the last round of tiles holds tiles % cus of them.
+    // If that is at most half the chip, those tiles are cut along K into as many parts as fill it,
+    // each part writes its partial tile to scratch, and a small kernel adds the parts up in order
+    // (the same sums in a different association; deterministic).
+    const int tail = cus > 0 ? tiles % cus : 0;
+    int parts = 1;
+    if (partial && tail > 0 && 2 * tail <= cus) {
+        parts = cus / tail;
+        if (parts > 8) parts = 8;
+        const int kt = n_cp / CfgBig::BK;
+        if (parts > kt / 16) parts = kt / 16;          // at least 16 slices per part
+        if ((size_t)tail * parts * CfgBig::BM * CfgBig::BN * 4 > mfma_dw_partial_bytes()) parts = 1;
+    }
+    if (parts < 2) {
+        launch<CfgBig, A_BLK_KM>(G, Vp, HcT, n_cp, V, D, n_cp, e, st);
+        return;
+    }
+    launch<CfgBig, A_BLK_KM>(G, Vp, HcT, n_cp, V, D, n_cp, e, st, 0, tiles - tail, 1);
+    EpiStoreDW ep = e;
+    ep.partial = partial;
+    launch<CfgBig, A_BLK_KM>(G, Vp, HcT, n_cp, V, D, n_cp, ep, st, tiles - tail, tail, parts);
+    sum_partial_tiles_kernel<CfgBig><<<dim3(tail, CfgBig::BM / 16), 256, 0, st>>>(
+        partial, tiles - tail, parts, tiles_m, tiles_n, reinterpret_cast<float*>(out.C), out.ldc, V, D, out.accumulate);
 }
 
 }  // namespace dppo

@@ -52,6 +52,7 @@ struct TileCtx {
     int m0, n0;        // first row / column of this wavefront's sub-tile
     int bm0, bn0;      // first row / column of the workgroup tile
     int wave_m, wave_n, lane, tid;
+    int item;          // work item of the launch (= tile when the launch does not split K)
     char* smem;
 };
 
@@ -144,16 +145,31 @@ __host__ __device__ __forceinline__ size_t blk_offset(int64_t r, int64_t c, int6
     return (size_t)(r / BLK_R) * BLK_R * ld + (size_t)(c / BLK_C) * (BLK_R * BLK_C) + (r % BLK_R) * BLK_C + c % BLK_C;
 }
 
+// Tile walk: tiles are numbered in bands of GROUP_M tile rows, column by column inside a band.
+template <int GROUP_M>
+__host__ __device__ __forceinline__ void tile_coords(int tile, int tiles_m, int tiles_n, int& tm, int& tn) {
+    const int band_sz = GROUP_M * tiles_n;
+    const int band = tile / band_sz, in_band = tile % band_sz;
+    const int first_m = band * GROUP_M;
+    const int gm = (tiles_m - first_m) < GROUP_M ? (tiles_m - first_m) : GROUP_M;
+    tm = first_m + in_band % gm;
+    tn = in_band / gm;
+}
+
+// A launch covers gridDim.x work items: item i is part i % k_parts of tile tile0 + i / k_parts,
+// and part p of a tile computes the k-slices [p KT / k_parts, (p + 1) KT / k_parts) of it
+// (k_parts = 1: whole tiles).
 template <class Cfg, class Epi, int AM = A_ROWS>
 __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __restrict__ A, int64_t lda,
                                                           const uint16_t* __restrict__ B, int64_t ldb, int M,
-                                                          int N, int K, int tiles_m, int tiles_n, Epi epi) {
+                                                          int N, int K, int tiles_m, int tiles_n, int tile0,
+                                                          int k_parts, Epi epi) {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     constexpr bool A_KM = AM == A_BLK_KM;
     constexpr int MI = Cfg::MI, NI = Cfg::NI, KK = Cfg::KK, LPS = Cfg::LPS;
     constexpr int ROWB = Cfg::ROWB, CPR = Cfg::CPR;
 
-    const int total = tiles_m * tiles_n;
+    const int total = gridDim.x;
     int logical;
     {
         const int bid = blockIdx.x;
@@ -162,15 +178,10 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
         logical = (xcd < rem) ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
     }
     int tm, tn;
-    {
-        constexpr int GROUP_M = Cfg::GROUP_M;
-        const int band_sz = GROUP_M * tiles_n;
-        const int band = logical / band_sz, in_band = logical % band_sz;
-        const int first_m = band * GROUP_M;
-        const int gm = (tiles_m - first_m) < GROUP_M ? (tiles_m - first_m) : GROUP_M;
-        tm = first_m + in_band % gm;
-        tn = in_band / gm;
-    }
+    tile_coords<Cfg::GROUP_M>(tile0 + logical / k_parts, tiles_m, tiles_n, tm, tn);
+    const int k_part = logical % k_parts;
+    const int kt_lo = (int)((int64_t)k_part * (K / Cfg::BK) / k_parts);
+    const int kt_hi = (int)((int64_t)(k_part + 1) * (K / Cfg::BK) / k_parts);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps LDS targets in SGPRs
     const int wave_m = wave % Cfg::WGM, wave_n = wave / Cfg::WGM;
@@ -206,10 +217,11 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
     // Issues load i of slice kt: i < B_LD is a B load into B-ring buffer bufb, the others are A loads
     // into A-ring buffer bufa. B goes first, so that at the next barrier "all but the newest A_LD
     // loads" means: this slice's B loads have landed, its A loads (due one slice later) may not have.
-    auto issue_load = [&](int bufa, int bufb, int kt, int i) {
+    auto issue_load = [&](int bufa, int bufb, int kt_rel, int i) {
+        const int64_t kt = kt_lo + kt_rel;
         const size_t koff = (size_t)kt * Cfg::BK;
-        const size_t koff_a = A_KM ? blk_offset((int64_t)kt * Cfg::BK, 0, lda)
-                              : AM == A_BLK_ROWS ? blk_offset(0, (int64_t)kt * Cfg::BK, lda) : koff;
+        const size_t koff_a = A_KM ? blk_offset(kt * Cfg::BK, 0, lda)
+                              : AM == A_BLK_ROWS ? blk_offset(0, kt * Cfg::BK, lda) : koff;
         const bool isA = i >= Cfg::B_LD;
         const int ii = isA ? i - Cfg::B_LD : i;
         char* dst = smem + (isA ? bufa * Cfg::A_BYTES : Cfg::B_RING + bufb * Cfg::B_BYTES) + (ii * Cfg::NW + wave) * 1024;
@@ -267,7 +279,7 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
 #pragma unroll
             for (int j = 0; j < 4; ++j) acc[mi][ni][j] = 0.0f;
 
-    const int KT = K / Cfg::BK;
+    const int KT = kt_hi - kt_lo;
     constexpr int SA = Cfg::SA, SB = Cfg::SB, A_LD = Cfg::A_LD, B_LD = Cfg::B_LD;
     // Slice kt has its A part in A-ring buffer kt % SA and its B part in B-ring buffer kt % SB. The
     // barrier at the last k-step of slice kt releases both buffers of slice kt, and the loads
@@ -371,7 +383,7 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
     c.M = M; c.N = N; c.tm = tm; c.tn = tn;
     c.bm0 = bm0; c.bn0 = bn0;
     c.m0 = bm0 + wave_m * Cfg::WTM; c.n0 = bn0 + wave_n * Cfg::WTN;
-    c.wave_m = wave_m; c.wave_n = wave_n; c.lane = lane; c.tid = tid; c.smem = smem;
+    c.wave_m = wave_m; c.wave_n = wave_n; c.lane = lane; c.tid = tid; c.item = logical; c.smem = smem;
     epi.template run<Cfg>(acc, c);
 }
 
@@ -388,6 +400,8 @@ template <int KIND>
 struct EpiStore {
     float* Cf; uint16_t* Cb; int64_t ldc; int accumulate; const int32_t* row_map; int64_t row_base;
     const float* row_scale;   // KIND 1: output row m is multiplied by row_scale[m] if not NULL
+    float* partial;           // KIND 0: if not NULL, work item i stores its whole BM x BN tile, row-major, at
+                              // partial + i * BM * BN instead (launches that split K; summed up by a second kernel)
 
     template <class Cfg>
     __device__ __forceinline__ void run(f32x4 (&acc)[Cfg::MI][Cfg::NI], const TileCtx& c) const {
@@ -418,7 +432,11 @@ struct EpiStore {
 #pragma unroll 4
                 for (int r = c.tid / VPR; r < HALF; r += RPP) {
                     const int row = c.bm0 + h * HALF + r;
-                    if (row < c.M && col < c.N) {
+                    if (partial) {
+                        *reinterpret_cast<f32x4v*>(partial + (size_t)c.item * (Cfg::BM * Cfg::BN) +
+                                                   (size_t)(h * HALF + r) * Cfg::BN + cv * 4) =
+                            *reinterpret_cast<const f32x4v*>(c.smem + r * PITCH + cv * 16);
+                    } else if (row < c.M && col < c.N) {
                         f32x4v v = *reinterpret_cast<const f32x4v*>(c.smem + r * PITCH + cv * 16);
                         f32x4v* dst = reinterpret_cast<f32x4v*>(Cf + (size_t)row * ldc + col);
                         if (accumulate) v += *dst;

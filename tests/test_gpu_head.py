@@ -110,6 +110,14 @@ def test_vocab_and_token_tails(lib):
     _run_case(lib, case, TOL["f32"])
 
 
+def test_long_chunk_with_few_output_tiles(lib):
+    # 8400 loss tokens against a dW of 8 x 1 tiles: the dW GEMM's last (only) round of tiles is
+    # nearly empty, so its tiles are cut along the token axis and summed by the second kernel
+    case = _case("small", 8400, dtype="bf16", D=256, V=2000)
+    assert case.pk["N"] >= 8300
+    _run_case(lib, case, TOL["bf16"])
+
+
 def test_clipping_zero_advantage_and_single_token_sequences(lib):
     rng = np.random.default_rng(8)
     # hand-built batch: constant groups (A = 0), one-token completions, both advantage signs
