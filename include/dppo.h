@@ -189,8 +189,12 @@ int dppo_token_logprob(const dppo_head_shape* shape,
  * Optional outputs: logp[N]; seq_loss[S] (token-mean loss of each sequence);
  * stats[4] = {mean KL over loss tokens, fraction of tokens whose surrogate gradient is
  * clipped away, N, 0}. loss is one float on the device.
- * recompute_logits = 0 keeps one chunk of logits in the workspace as fp16 (needs
- * |z| < 65504); 1 runs the vocabulary GEMM a second time in the backward instead.
+ * recompute_logits = 0 (bfloat16) keeps, per chunk of tokens, exp(z - target logit) as bfloat16 in
+ * the workspace, which the backward GEMMs turn into softmax gradients by a row scale (tokens whose
+ * target has a log-prob below about -69 take a slower exact path); 1 runs the vocabulary GEMM a
+ * second time in the backward instead and keeps the gradient entries themselves.
+ * The call is asynchronous on `stream` and deterministic, except that the log-probs of tokens on
+ * that exact path are summed with atomic adds (last bits may vary between runs).
  *
  * Variants for the other objectives the method is plugged into (Sec. 5, robustness across RL
  * algorithms; the paper names them without formulas, these are this library's readings):
@@ -252,7 +256,7 @@ int dppo_token_norm_coef(int32_t Q, int32_t G, const int32_t* comp_len, const fl
  */
 enum {
     DPPO_STAGE_LOGITS_GEMM = 0, /* vocabulary GEMM with the online max / sum-exp epilogue */
-    DPPO_STAGE_GRAD_LOGITS = 1, /* softmax-gradient pass over the stored logits chunk     */
+    DPPO_STAGE_GRAD_LOGITS = 1, /* softmax-gradient pass over the stored chunk (float32), row scales (bfloat16) */
     DPPO_STAGE_DH_GEMM = 2,     /* dH = G W                                               */
     DPPO_STAGE_DW_GEMM = 3,     /* dW += G^T H                                            */
     DPPO_N_STAGES = 4
