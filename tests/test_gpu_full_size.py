@@ -134,5 +134,35 @@ def test_whole_batch_sampled_against_oracle(lib, name):
     assert abs(h_dh - w_dw) <= 2e-3 * max(h_mag, w_mag)
     stats = out["stats"].cpu().numpy()
     assert stats[2] == N and 0.0 < stats[1] < 1.0 and stats[0] > 0.0
+
+    # (e) sampled dW rows, dW[v] = sum_n c_n (1[y_n = v] - exp(z_nv - lse_n)) H_n, in float64 by plain
+    # tensor arithmetic over ALL loss tokens; c_n by the oracle's token terms from the log-probs
+    # that (a) sampled, lse_n = z_{n,y_n} - logp_n. Rows from the first tile, the middle, the
+    # frequent targets, and the last tile rows (the tiles of the dW GEMM's last round, which are
+    # computed in K-split parts).
+    y_all = ids_np[loss_pos + 1]
+    s_all = np.searchsorted(loss_cu, np.arange(N), side="right") - 1
+    _, g_all, _, _ = O.token_terms(logp_gpu.astype(np.float64), old_np.astype(np.float64), ref_np.astype(np.float64),
+                                   adv_s[s_all].astype(np.float64), wl.clip_eps, wl.clip_eps, wl.kl_beta)
+    c_all = coef_s[s_all].astype(np.float64) / np.diff(loss_cu)[s_all] * g_all
+    vs = np.unique(np.concatenate([[0, 255, 256, wl.V // 2, wl.V - 1, wl.V - 300, max(wl.V - 1000, 0)],
+                                   np.bincount(y_all, minlength=wl.V).argsort()[-2:]]))
+    Wv = W[torch.as_tensor(vs, device=DEV).long()].double()
+    ref_rows = torch.zeros((len(vs), wl.D), dtype=torch.float64, device=DEV)
+    lp_t, c_t = torch.as_tensor(logp_gpu, device=DEV).double(), torch.as_tensor(c_all, device=DEV)
+    y_t, vs_t = torch.as_tensor(y_all, device=DEV).long(), torch.as_tensor(vs, device=DEV).long()
+    lpos_t = torch.as_tensor(loss_pos, device=DEV).long()
+    for i in range(0, N, 1 << 15):
+        j = min(N, i + (1 << 15))
+        Hn = H[lpos_t[i:j]].double()
+        zy = (Hn * W[y_t[i:j]].double()).sum(dim=1)
+        lse_n = zy - lp_t[i:j]
+        Pn = torch.exp(Hn @ Wv.T - lse_n[:, None])
+        Gn = c_t[i:j, None] * ((y_t[i:j, None] == vs_t[None, :]).double() - Pn)
+        ref_rows += Gn.T @ Hn
+    got_rows = dW[vs_t].double()
+    assert float((got_rows - ref_rows).norm() / ref_rows.norm()) <= 1e-2
+    row_err = (got_rows - ref_rows).norm(dim=1) / ref_rows.norm(dim=1).clamp_min(1e-30)
+    assert float(row_err.max()) <= 3e-2, row_err
     del out, H, W, dW
     torch.cuda.empty_cache()

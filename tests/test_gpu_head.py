@@ -187,15 +187,14 @@ def test_objective_variants_fp32(lib):
 def test_targets_of_vanishing_probability(lib):
     # The bf16 backward pass keeps exp(z - z_target) per stored entry; rows whose target has a
     # log-prob below about -69 overflow that and must come out right through the exact row path,
-    # next to rows that stay on the fast path.
-    case = _case("tiny", None, dtype="bf16", D=128, V=777)
-    lp0, _ = case.oracle_logprob()
-    case._H64 = None
-    rows = case.pk["loss_pos"][::3]
-    case.H[torch.as_tensor(rows, device=DEV).long()] *= 64.0       # exact in bf16
-    logp_ref, _ = case.oracle_logprob()
-    assert (logp_ref < -100).sum() >= 5 and (logp_ref > -40).sum() >= 5
-    _run_case(lib, case, TOL["bf16"])
+    # next to rows that stay on the fast path. Second shape: D beyond one 2048-column slab of that path.
+    for D, V, factor in ((128, 777, 64.0), (2304, 300, 16.0)):
+        case = _case("tiny", None, dtype="bf16", D=D, V=V)
+        rows = case.pk["loss_pos"][::3]
+        case.H[torch.as_tensor(rows, device=DEV).long()] *= factor       # exact in bf16
+        logp_ref, _ = case.oracle_logprob()
+        assert (logp_ref < -100).sum() >= 5 and (logp_ref > -40).sum() >= 5
+        _run_case(lib, case, TOL["bf16"])
 
 
 def test_coincident_policies(lib):
