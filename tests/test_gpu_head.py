@@ -115,7 +115,12 @@ def test_long_chunk_with_few_output_tiles(lib):
     # nearly empty, so its tiles are cut along the token axis and summed by the second kernel
     case = _case("small", 8400, dtype="bf16", D=256, V=2000)
     assert case.pk["N"] >= 8300
-    _run_case(lib, case, TOL["bf16"])
+    out, _ = _run_case(lib, case, TOL["bf16"])
+    # the summing kernel also honours accumulation into an existing dW
+    acc = out["dW"].clone()
+    lib.dppo_loss_fwd_bwd(case.H, case.W, case.ids, case.loss_pos, case.loss_cu, case.seq_adv, case.seq_coef,
+                          case.logp_old, case.logp_ref, dW=acc, accumulate_dW=True)
+    assert torch.equal(acc, 2.0 * out["dW"])
 
 
 def test_clipping_zero_advantage_and_single_token_sequences(lib):
