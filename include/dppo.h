@@ -191,7 +191,7 @@ int dppo_token_logprob(const dppo_head_shape* shape,
  * clipped away, N, 0}. loss is one float on the device.
  * recompute_logits = 0 (bfloat16) keeps, per chunk of tokens, exp(z - target logit) as bfloat16 in
  * the workspace, which the backward GEMMs turn into softmax gradients by a row scale (tokens whose
- * target has a log-prob below about -69 take a slower exact path); 1 runs the vocabulary GEMM a
+ * target has a log-prob below about -34 take a slower exact path); 1 runs the vocabulary GEMM a
  * second time in the backward instead and keeps the gradient entries themselves.
  * The call is asynchronous on `stream` and deterministic, except that the log-probs of tokens on
  * that exact path are summed with atomic adds (last bits may vary between runs).

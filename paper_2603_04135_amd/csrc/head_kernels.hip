@@ -134,10 +134,12 @@ __global__ __launch_bounds__(256) void combine_logprob_kernel(const float2* __re
 
 // Same split of the work for the GEMM that stores exponentials: part[tile][n] = (max z, sum of
 // exp(z - bref[n])) with one reference per token, so the sums of the tiles add up and
-// lse = bref + log(sum). A sum so large that the stored exponentials, or the sums the backward
-// GEMMs form of them, could leave the float range (reference = target logit: a target token with
-// log-prob below about -69) puts the token on the redo list instead.
-constexpr float EXP_SUM_LIMIT = 1e30f;
+// lse = bref + log(sum). With the target logit as reference the sum is 1 / p(target), the stored
+// exponentials reach that size and the row scale c p(target) shrinks by it; beyond 1e15 (a target
+// token with log-prob below about -34.5) the scaled hidden-state rows of the dW operand would
+// approach the bottom of the bf16 range for small loss weights, so the token goes on the redo
+// list instead and is redone against its row maximum.
+constexpr float EXP_SUM_LIMIT = 1e15f;
 __global__ __launch_bounds__(256) void combine_exp_kernel(const float2* __restrict__ part, int32_t n_tiles,
                                                           const float* __restrict__ zy,
                                                           const float* __restrict__ bref, int64_t n0, int32_t n_c,

@@ -191,14 +191,18 @@ def test_objective_variants_fp32(lib):
 
 def test_targets_of_vanishing_probability(lib):
     # The bf16 backward pass keeps exp(z - z_target) per stored entry; rows whose target has a
-    # log-prob below about -69 overflow that and must come out right through the exact row path,
-    # next to rows that stay on the fast path. Second shape: D beyond one 2048-column slab of that path.
-    for D, V, factor in ((128, 777, 64.0), (2304, 300, 16.0)):
+    # log-prob below about -34.5 leave the range that scheme is used in and must come out right through
+    # the exact row path (some of them overflow the stored exponentials outright), next to rows just
+    # above the limit, with stored exponentials up to e^34, and ordinary rows on the fast path.
+    # Second shape: D beyond one 2048-column slab of the exact path.
+    for D, V, factor, mid in ((128, 777, 64.0, 16.0), (2304, 300, 16.0, 4.0)):
         case = _case("tiny", None, dtype="bf16", D=D, V=V)
-        rows = case.pk["loss_pos"][::3]
-        case.H[torch.as_tensor(rows, device=DEV).long()] *= factor       # exact in bf16
+        lp = torch.as_tensor(case.pk["loss_pos"], device=DEV).long()
+        case.H[lp[::3]] *= factor       # exact in bf16
+        case.H[lp[1::3]] *= mid
         logp_ref, _ = case.oracle_logprob()
-        assert (logp_ref < -100).sum() >= 5 and (logp_ref > -40).sum() >= 5
+        assert (logp_ref < -100).sum() >= 5 and (logp_ref > -15).sum() >= 5
+        assert ((logp_ref > -34) & (logp_ref < -20)).sum() >= 5 and ((logp_ref > -69) & (logp_ref < -35)).sum() >= 5
         _run_case(lib, case, TOL["bf16"])
 
 
