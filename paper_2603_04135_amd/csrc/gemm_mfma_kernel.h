@@ -26,8 +26,9 @@
 // lanes x 16 bytes contiguously, so the swizzle is applied on the global-address side: each lane
 // fetches the chunk that belongs at the LDS position it will be written to.
 //
-// Workgroup ids are remapped so that the workgroups resident on one XCD (ids congruent mod 8)
-// cover a compact GROUP_M x n block of tiles and share operand panels in that XCD's L2.
+// Workgroup ids are remapped so that the 32 workgroups resident on one XCD (ids congruent mod 8)
+// at any time are 32 consecutive tiles of the walk, a compact GROUP_M x 8 block of tiles that
+// shares operand panels in that XCD's L2.
 #pragma once
 #include <type_traits>
 
@@ -44,7 +45,7 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) char lds_char;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int NUM_XCD = 8;
+constexpr int NUM_XCD = 8, CU_PER_XCD = 32;   // MI355X: 8 XCDs of 32 compute units, one L2 each
 
 struct TileCtx {
     int M, N;          // logical output size
@@ -169,13 +170,21 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
     constexpr int MI = Cfg::MI, NI = Cfg::NI, KK = Cfg::KK, LPS = Cfg::LPS;
     constexpr int ROWB = Cfg::ROWB, CPR = Cfg::CPR;
 
+    // Workgroup id -> work item. Ids congruent mod NUM_XCD run on the same XCD, in id order, one
+    // per compute unit at a time, and all tiles of a launch take about the same time: the j-th
+    // "round" of an XCD is its workgroups 32 j .. 32 j + 31. Round j of XCD x gets the 32
+    // consecutive items of group 8 j + x, so that what shares that XCD's L2 at any time is one
+    // compact block of the tile walk (a contiguous range of items per XCD puts round boundaries
+    // anywhere in the bands: 63 instead of 48 GB of L2 misses per dH launch, 3.4 % slower).
     const int total = gridDim.x;
-    int logical;
+    int logical = blockIdx.x;
     {
+        constexpr int ROUND = NUM_XCD * CU_PER_XCD;
         const int bid = blockIdx.x;
-        const int xcd = bid % NUM_XCD, idx = bid / NUM_XCD;
-        const int per = total / NUM_XCD, rem = total % NUM_XCD;
-        logical = (xcd < rem) ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
+        if (bid < total / ROUND * ROUND) {       // the last, partial round keeps the identity
+            const int xcd = bid % NUM_XCD, idx = bid / NUM_XCD;
+            logical = ((idx / CU_PER_XCD) * NUM_XCD + xcd) * CU_PER_XCD + idx % CU_PER_XCD;
+        }
     }
     int tm, tn;
     tile_coords<Cfg::GROUP_M>(tile0 + logical / k_parts, tiles_m, tiles_n, tm, tn);
