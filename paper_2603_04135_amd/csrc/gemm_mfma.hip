@@ -20,13 +20,13 @@ constexpr int lds_request() {
 
 // Launches the tiles [tile0, tile0 + n_tiles) of the tile walk, each cut into k_parts work items
 // along K; n_tiles < 0: all tiles.
-template <class Cfg, int AM = A_ROWS, class Epi>
+template <class Cfg, int AM = A_ROWS, int MAP = WG_ROUNDS, class Epi>
 void launch(const void* A, int64_t lda, const void* B, int64_t ldb, int M, int N, int K, const Epi& epi,
             hipStream_t st, int tile0 = 0, int n_tiles = -1, int k_parts = 1) {
     const int tiles_m = (int)ceil_div(M, Cfg::BM), tiles_n = (int)ceil_div(N, Cfg::BN);
     if (n_tiles < 0) n_tiles = tiles_m * tiles_n - tile0;
     if (n_tiles <= 0) return;
-    gemm_nt_kernel<Cfg, Epi, AM><<<dim3(n_tiles * k_parts), dim3(Cfg::NT), lds_request<Cfg, Epi>(), st>>>(
+    gemm_nt_kernel<Cfg, Epi, AM, MAP><<<dim3(n_tiles * k_parts), dim3(Cfg::NT), lds_request<Cfg, Epi>(), st>>>(
         reinterpret_cast<const uint16_t*>(A), lda, reinterpret_cast<const uint16_t*>(B), ldb, M, N, K, tiles_m,
         tiles_n, tile0, k_parts, epi);
 }
@@ -55,9 +55,9 @@ __global__ __launch_bounds__(256) void sum_partial_tiles_kernel(const float* __r
     }
 }
 
-template <class Cfg, class Epi, int AM = A_ROWS>
+template <class Cfg, class Epi, int AM = A_ROWS, int MAP = WG_ROUNDS>
 hipError_t allow_lds() {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_kernel<Cfg, Epi, AM>),
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_kernel<Cfg, Epi, AM, MAP>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_request<Cfg, Epi>());
 }
 
@@ -70,7 +70,7 @@ int mfma_setup() {
         int dev = 0;
         hipError_t e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&g_compute_units, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e == hipSuccess) e = allow_lds<CfgBig, EpiStoreDW, A_BLK_KM>();
+        if (e == hipSuccess) e = allow_lds<CfgBig, EpiStoreDW, A_BLK_KM, WG_RANGES>();
         if (e == hipSuccess) e = allow_lds<CfgBig, EpiStoreDH, A_BLK_ROWS>();
         if (e == hipSuccess) e = allow_lds<CfgBig, EpiLogits>();
         if (e == hipSuccess) e = allow_lds<CfgBig, EpiLogitsExp>();
@@ -139,13 +139,13 @@ void launch_mfma_dw(const void* G, int32_t Vp, const void* HcT, int32_t n_cp, in
         if ((size_t)tail * parts * CfgBig::BM * CfgBig::BN * 4 > mfma_dw_partial_bytes()) parts = 1;
     }
     if (parts < 2) {
-        launch<CfgBig, A_BLK_KM>(G, Vp, HcT, n_cp, V, D, n_cp, e, st);
+        launch<CfgBig, A_BLK_KM, WG_RANGES>(G, Vp, HcT, n_cp, V, D, n_cp, e, st);
         return;
     }
-    launch<CfgBig, A_BLK_KM>(G, Vp, HcT, n_cp, V, D, n_cp, e, st, 0, tiles - tail, 1);
+    launch<CfgBig, A_BLK_KM, WG_RANGES>(G, Vp, HcT, n_cp, V, D, n_cp, e, st, 0, tiles - tail, 1);
     EpiStoreDW ep = e;
     ep.partial = partial;
-    launch<CfgBig, A_BLK_KM>(G, Vp, HcT, n_cp, V, D, n_cp, ep, st, tiles - tail, tail, parts);
+    launch<CfgBig, A_BLK_KM, WG_RANGES>(G, Vp, HcT, n_cp, V, D, n_cp, ep, st, tiles - tail, tail, parts);
     sum_partial_tiles_kernel<CfgBig><<<dim3(tail, CfgBig::BM / 16), 256, 0, st>>>(
         partial, tiles - tail, parts, tiles_m, tiles_n, reinterpret_cast<float*>(out.C), out.ldc, V, D, out.accumulate);
 }

@@ -160,7 +160,8 @@ __host__ __device__ __forceinline__ void tile_coords(int tile, int tiles_m, int 
 // A launch covers gridDim.x work items: item i is part i % k_parts of tile tile0 + i / k_parts,
 // and part p of a tile computes the k-slices [p KT / k_parts, (p + 1) KT / k_parts) of it
 // (k_parts = 1: whole tiles).
-template <class Cfg, class Epi, int AM = A_ROWS>
+enum { WG_ROUNDS = 0, WG_RANGES = 1 };
+template <class Cfg, class Epi, int AM = A_ROWS, int MAP = WG_ROUNDS>
 __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __restrict__ A, int64_t lda,
                                                           const uint16_t* __restrict__ B, int64_t ldb, int M,
                                                           int N, int K, int tiles_m, int tiles_n, int tile0,
@@ -172,18 +173,25 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
 
     // Workgroup id -> work item. Ids congruent mod NUM_XCD run on the same XCD, in id order, one
     // per compute unit at a time, and all tiles of a launch take about the same time: the j-th
-    // "round" of an XCD is its workgroups 32 j .. 32 j + 31. Round j of XCD x gets the 32
-    // consecutive items of group 8 j + x, so that what shares that XCD's L2 at any time is one
-    // compact block of the tile walk (a contiguous range of items per XCD puts round boundaries
-    // anywhere in the bands: 63 instead of 48 GB of L2 misses per dH launch, 3.4 % slower).
+    // "round" of an XCD is its workgroups 32 j .. 32 j + 31.
+    // WG_ROUNDS: round j of XCD x gets the 32 consecutive items of group 8 j + x, so that what
+    // shares that XCD's L2 at any time is one compact block of the tile walk.
+    // WG_RANGES: every XCD gets one contiguous range of items (round boundaries then fall
+    // anywhere in the bands, but consecutive rounds of an XCD are neighbours in the walk).
+    // Measured L2 misses per launch, rounds against ranges: dH 52 against 60 GB (3 % faster),
+    // vocabulary GEMM 38 against 45 GB, dW 55 against 47 GB (0.5 % slower): dW uses ranges.
     const int total = gridDim.x;
     int logical = blockIdx.x;
     {
-        constexpr int ROUND = NUM_XCD * CU_PER_XCD;
         const int bid = blockIdx.x;
-        if (bid < total / ROUND * ROUND) {       // the last, partial round keeps the identity
-            const int xcd = bid % NUM_XCD, idx = bid / NUM_XCD;
-            logical = ((idx / CU_PER_XCD) * NUM_XCD + xcd) * CU_PER_XCD + idx % CU_PER_XCD;
+        const int xcd = bid % NUM_XCD, idx = bid / NUM_XCD;
+        if (MAP == WG_ROUNDS) {
+            constexpr int ROUND = NUM_XCD * CU_PER_XCD;
+            if (bid < total / ROUND * ROUND)         // the last, partial round keeps the identity
+                logical = ((idx / CU_PER_XCD) * NUM_XCD + xcd) * CU_PER_XCD + idx % CU_PER_XCD;
+        } else {
+            const int per = total / NUM_XCD, rem = total % NUM_XCD;
+            logical = (xcd < rem) ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
         }
     }
     int tm, tn;
