@@ -256,6 +256,27 @@ def test_identity_rows_chunking_accumulation_and_recompute(lib):
     assert np.abs(lpi.cpu().numpy() - logp_ref).max() <= 2e-3
 
 
+def test_empty_batch(lib):
+    # every completion pruned: packed tokens may exist, loss tokens do not
+    for dtype in (torch.bfloat16, torch.float32):
+        T, D, V = 37, 128, 300
+        H = torch.randn(T, D, device=DEV).to(dtype)
+        W = torch.randn(V, D, device=DEV).to(dtype)
+        ids = torch.zeros(T, dtype=torch.int32, device=DEV)
+        none_i = torch.zeros(0, dtype=torch.int32, device=DEV)
+        none_f = torch.zeros(0, dtype=torch.float32, device=DEV)
+        cu = torch.zeros(1, dtype=torch.int32, device=DEV)
+        logp, lse = lib.dppo_token_logprob(H, W, ids, none_i)
+        assert logp.numel() == 0 and lse.numel() == 0
+        out = lib.dppo_loss_fwd_bwd(H, W, ids, none_i, cu, none_f, none_f, none_f, none_f)
+        torch.cuda.synchronize()
+        assert float(out["loss"]) == 0.0 and out["seq_loss"].numel() == 0 and float(out["stats"][2]) == 0.0
+        assert not bool(out["dH"].any()) and not bool(out["dW"].any())
+        keep = torch.full((V, D), 3.0, device=DEV)
+        lib.dppo_loss_fwd_bwd(H, W, ids, none_i, cu, none_f, none_f, none_f, none_f, dW=keep, accumulate_dW=True)
+        assert bool((keep == 3.0).all())
+
+
 def test_hip_graph_replays_match_eager(lib):
     # The entry points only enqueue kernels on the caller's stream (no allocation, no
     # synchronisation, no memset nodes), so a whole loss step can be captured once and replayed.
