@@ -204,6 +204,20 @@ def test_targets_of_vanishing_probability(lib):
         assert (logp_ref < -100).sum() >= 5 and (logp_ref > -15).sum() >= 5
         assert ((logp_ref > -34) & (logp_ref < -20)).sum() >= 5 and ((logp_ref > -69) & (logp_ref < -35)).sum() >= 5
         _run_case(lib, case, TOL["bf16"])
+    # several chunks (smallest workspace), each with its own list of rows to redo
+    case = _case("small", 1500)
+    lp = torch.as_tensor(case.pk["loss_pos"], device=DEV).long()
+    case.H[lp[::5]] *= 64.0
+    logp_ref, _ = case.oracle_logprob()
+    assert (logp_ref < -100).sum() >= 100
+    case.set_behaviour_logps(logp_ref)
+    ref = case.oracle_loss()
+    T, N, D, V = case.pk["T"], case.pk["N"], case.wl.D, case.wl.V
+    ws = lib.alloc_workspace(lib.dppo_workspace_min_bytes(T, N, D, V, 1, True), DEV)
+    out = lib.dppo_loss_fwd_bwd(case.H, case.W, case.ids, case.loss_pos, case.loss_cu, case.seq_adv, case.seq_coef,
+                                case.logp_old, case.logp_ref, ws=ws)
+    assert np.abs(out["logp"].cpu().numpy() - ref["logp"]).max() <= TOL["bf16"]["logp"]
+    assert rel_fro(to_np64(out["dH"]), ref["dH"]) <= 1e-2 and rel_fro(to_np64(out["dW"]), ref["dW"]) <= 1e-2
 
 
 def test_coincident_policies(lib):
