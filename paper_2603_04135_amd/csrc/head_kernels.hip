@@ -272,20 +272,68 @@ __global__ void softmax_scale_kernel(const int32_t* __restrict__ y, const float*
         __builtin_bit_cast(uint16_t, e);
 }
 
-// dstT[c, r] = bf16(scale[r] * src[r, c]) for a bf16 [n_rows, n_cols] matrix (both multiples of 64).
-__global__ __launch_bounds__(256) void scale_transpose_kernel(const uint16_t* __restrict__ src, int64_t ld_src,
-                                                              const float* __restrict__ scale,
-                                                              uint16_t* __restrict__ dstT, int64_t ld_dstT) {
-    __shared__ uint16_t tile[64][65];
+// bf16 transpose by 16-byte accesses: dstT[c, r] = scale[r] * src[r, c] (scale NULL = 1) for
+// r < rows_out, c < cols; source rows >= rows_valid read as zero. cols and rows_out are
+// multiples of 64, all pointers and pitches multiples of 8 elements. A 64 x 64 tile goes through
+// LDS; every thread loads and stores whole 8-element vectors.
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __restrict__ src, int64_t ld_src,
+                                                             int32_t rows_valid, const float* __restrict__ scale,
+                                                             uint16_t* __restrict__ dstT, int64_t ld_dstT) {
+    __shared__ uint16_t tile[64][64 + 2];
     const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int rr = ty; rr < 64; rr += 4) {
-        const float sc = scale ? scale[r0 + rr] : 1.0f;
-        const __bf16 v = (__bf16)(sc * bf16_to_f32(src[(int64_t)(r0 + rr) * ld_src + c0 + tx]));
-        tile[rr][tx] = __builtin_bit_cast(uint16_t, v);
+    const int vec = threadIdx.x & 7, line = threadIdx.x >> 3;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int rr = line + pass * 32, r = r0 + rr;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (r < rows_valid) v = *reinterpret_cast<const uint4*>(src + (int64_t)r * ld_src + c0 + vec * 8);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        if (scale && r < rows_valid) {
+            const float sc = scale[r];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const __bf16 lo = (__bf16)(sc * __uint_as_float(w[k] << 16));
+                const __bf16 hi = (__bf16)(sc * __uint_as_float(w[k] & 0xffff0000u));
+                tile[rr][vec * 8 + 2 * k] = __builtin_bit_cast(uint16_t, lo);
+                tile[rr][vec * 8 + 2 * k + 1] = __builtin_bit_cast(uint16_t, hi);
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                tile[rr][vec * 8 + 2 * k] = (uint16_t)(w[k] & 0xffffu);
+                tile[rr][vec * 8 + 2 * k + 1] = (uint16_t)(w[k] >> 16);
+            }
+        }
     }
     __syncthreads();
-    for (int cc = ty; cc < 64; cc += 4) dstT[(int64_t)(c0 + cc) * ld_dstT + r0 + tx] = tile[tx][cc];
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int cc = line + pass * 32;
+        uint32_t w[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            w[k] = (uint32_t)tile[vec * 8 + 2 * k][cc] | ((uint32_t)tile[vec * 8 + 2 * k + 1][cc] << 16);
+        *reinterpret_cast<uint4*>(dstT + (int64_t)(c0 + cc) * ld_dstT + r0 + vec * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+// bf16 row gather by 16-byte vectors: dst[r] = src[row(r)] for r < n_valid (row through the
+// optional index, clamped), zero rows up to n_rows_out. vec_per_row = D / 8.
+__global__ __launch_bounds__(256) void gather_rows_bf16_kernel(const uint4* __restrict__ src, int32_t vec_per_row,
+                                                               const int32_t* __restrict__ row_index,
+                                                               int64_t row_index_base, int64_t src_row0,
+                                                               int64_t src_rows_total, int32_t n_valid,
+                                                               int32_t n_rows_out, uint4* __restrict__ dst) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (int64_t)n_rows_out * vec_per_row) return;
+    const int32_t r = (int32_t)(i / vec_per_row), c = (int32_t)(i % vec_per_row);
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (r < n_valid) {
+        int64_t sr = row_index ? (int64_t)row_index[row_index_base + r] : src_row0 + r;
+        sr = sr < 0 ? 0 : (sr >= src_rows_total ? src_rows_total - 1 : sr);
+        v = src[sr * vec_per_row + c];
+    }
+    dst[i] = v;
 }
 
 // fp32 path: one workgroup per token over the stored logits row.
@@ -508,7 +556,12 @@ void launch_fill_zero(void* p, size_t bytes, hipStream_t st) {
 void launch_gather_rows(int dtype, const void* H, const int32_t* ids, const int32_t* loss_pos, int64_t T,
                         int32_t D, int32_t V, ChunkView cv, void* Hc, void* HcT, int32_t* y, hipStream_t st) {
     dim3 grid((unsigned)ceil_div(D, 64), (unsigned)(cv.n_cp / 64));
-    if (dtype == 1) {
+    if (dtype == 1 && HcT == nullptr && D % 8 == 0) {
+        const int64_t n_vec = (int64_t)cv.n_cp * (D / 8);
+        gather_rows_bf16_kernel<<<(unsigned)ceil_div(n_vec, 256), 256, 0, st>>>(
+            reinterpret_cast<const uint4*>(H), D / 8, loss_pos, cv.n0, cv.n0, T, cv.n_c, cv.n_cp,
+            reinterpret_cast<uint4*>(Hc));
+    } else if (dtype == 1) {
         gather_transpose_kernel<uint16_t><<<grid, 256, 0, st>>>(
             reinterpret_cast<const uint16_t*>(H), D, loss_pos, cv.n0, cv.n0, T, cv.n_c, D, cv.n_cp, D,
             reinterpret_cast<uint16_t*>(Hc), D, reinterpret_cast<uint16_t*>(HcT), cv.n_cp);
@@ -522,7 +575,10 @@ void launch_gather_rows(int dtype, const void* H, const int32_t* ids, const int3
 
 void launch_transpose_w(int dtype, const void* W, int32_t V, int32_t D, int32_t Vp, void* WT, hipStream_t st) {
     dim3 grid((unsigned)ceil_div(D, 64), (unsigned)ceil_div(Vp, 64));
-    if (dtype == 1) {
+    if (dtype == 1 && D % 64 == 0 && Vp % 64 == 0) {
+        transpose_bf16_kernel<<<grid, 256, 0, st>>>(reinterpret_cast<const uint16_t*>(W), D, V, nullptr,
+                                                    reinterpret_cast<uint16_t*>(WT), Vp);
+    } else if (dtype == 1) {
         gather_transpose_kernel<uint16_t><<<grid, 256, 0, st>>>(reinterpret_cast<const uint16_t*>(W), D, nullptr, 0,
                                                                 0, V, V, D, Vp, D, nullptr, 0,
                                                                 reinterpret_cast<uint16_t*>(WT), Vp);
@@ -575,8 +631,8 @@ void launch_softmax_scale(const int32_t* y, const float* zy, const float* bref, 
 void launch_scale_transpose_bf16(const void* Hc, const float* scale, int32_t n_cp, int32_t D, void* HcT,
                                  hipStream_t st) {
     dim3 grid((unsigned)(D / 64), (unsigned)(n_cp / 64));
-    scale_transpose_kernel<<<grid, 256, 0, st>>>(reinterpret_cast<const uint16_t*>(Hc), D, scale,
-                                                 reinterpret_cast<uint16_t*>(HcT), n_cp);
+    transpose_bf16_kernel<<<grid, 256, 0, st>>>(reinterpret_cast<const uint16_t*>(Hc), D, n_cp, scale,
+                                                reinterpret_cast<uint16_t*>(HcT), n_cp);
 }
 
 void launch_combine_logprob(const float2* part, int32_t n_tiles, const float* zy, ChunkView cv, float* lse_chunk,
