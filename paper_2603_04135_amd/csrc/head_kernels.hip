@@ -85,7 +85,21 @@ __global__ __launch_bounds__(256) void target_logit_kernel(const E* __restrict__
     const E* h = Hc + (size_t)n * D;
     const E* w = W + (size_t)y[n] * D;
     float s = 0.0f;
-    for (int d = lane; d < D; d += 64) s = fmaf(to_f32(h[d]), to_f32(w[d]), s);
+    if (sizeof(E) == 2 && D % 8 == 0) {          // bf16 rows (16-byte aligned): 8 elements per lane and step
+        const uint4* h8 = reinterpret_cast<const uint4*>(h);
+        const uint4* w8 = reinterpret_cast<const uint4*>(w);
+        for (int c = lane; c < D / 8; c += 64) {
+            const uint4 a = h8[c], b = w8[c];
+            const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                s = fmaf(__uint_as_float(aw[k] << 16), __uint_as_float(bw[k] << 16), s);
+                s = fmaf(__uint_as_float(aw[k] & 0xffff0000u), __uint_as_float(bw[k] & 0xffff0000u), s);
+            }
+        }
+    } else {
+        for (int d = lane; d < D; d += 64) s = fmaf(to_f32(h[d]), to_f32(w[d]), s);
+    }
     for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
     if (lane == 0) {
         zy[n] = s;
@@ -152,6 +166,7 @@ __global__ __launch_bounds__(256) void combine_exp_kernel(const float2* __restri
     const int n = blockIdx.x * 64 + lane;
     float m = -__builtin_inff(), s = 0.0f;
     if (n < n_cp) {
+#pragma unroll 8
         for (int t = q; t < n_tiles; t += 4) {
             const float2 p = part[(size_t)t * n_cp + n];
             m = fmaxf(m, p.x);
