@@ -6,9 +6,15 @@ namespace {
 using namespace mfma;
 
 // 256x256x64 tile, 2x4 wavefronts (128x64 each), 3 A slices and 2 B slices in flight (all 160 KB of
-// LDS), all loads of a slice issued in the k-step that frees its buffers, bands of 4 tile rows. The
-// blocked chunk layout (64 x 256 element blocks) is tied to this tile.
+// LDS), all loads of a slice issued in the k-step that frees its buffers. The blocked chunk layout
+// (64 x 256 element blocks) is tied to this tile. The GEMMs differ only in the band height of the
+// tile walk: 4 tile rows for the vocabulary GEMM (126 token tiles per row: 4 x 8 blocks per L2);
+// 1 for dH and dW, whose rows have only D / 256 = 10 tiles: the A panels there are pieces of the
+// 10 GB chunk that streams from HBM, and with one-row bands all 10 users of a panel are
+// consecutive tiles and run in the same round (bands of 4 x 10 tiles straddle the rounds of 32:
+// dH +1.6 %, dW +1.2 % in time).
 typedef PipeCfg<256, 256, 64, 2, 4, 2, 0, 1, 4, 1> CfgBig;
+typedef PipeCfg<256, 256, 64, 2, 4, 2, 0, 1, 1, 1> CfgGrad;
 
 // Dynamic LDS of a kernel: the operand slices, or the epilogue's staging area if that is larger.
 template <class Cfg, class Epi>
@@ -70,8 +76,8 @@ int mfma_setup() {
         int dev = 0;
         hipError_t e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&g_compute_units, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e == hipSuccess) e = allow_lds<CfgBig, EpiStoreDW, A_BLK_KM, WG_RANGES>();
-        if (e == hipSuccess) e = allow_lds<CfgBig, EpiStoreDH, A_BLK_ROWS>();
+        if (e == hipSuccess) e = allow_lds<CfgGrad, EpiStoreDW, A_BLK_KM, WG_RANGES>();
+        if (e == hipSuccess) e = allow_lds<CfgGrad, EpiStoreDH, A_BLK_ROWS>();
         if (e == hipSuccess) e = allow_lds<CfgBig, EpiLogits>();
         if (e == hipSuccess) e = allow_lds<CfgBig, EpiLogitsExp>();
         if (e == hipSuccess) e = allow_lds<CfgBig, EpiLogitsGrad>();
@@ -115,7 +121,7 @@ int launch_mfma_logits_grad(const void* W, int32_t V, int32_t D, const void* Hc,
 void launch_mfma_dh(const void* G, int32_t Vp, const void* WT, int32_t n_c, int32_t D, const float* row_scale,
                     const StoreSpec& out, hipStream_t st) {
     EpiStoreDH e{nullptr, reinterpret_cast<uint16_t*>(out.C), out.ldc, 0, out.row_map, out.row_base, row_scale, nullptr};
-    launch<CfgBig, A_BLK_ROWS>(G, Vp, WT, Vp, n_c, D, Vp, e, st);
+    launch<CfgGrad, A_BLK_ROWS>(G, Vp, WT, Vp, n_c, D, Vp, e, st);
 }
 
 size_t mfma_dw_partial_bytes() { return (size_t)256 * CfgBig::BM * CfgBig::BN * 4; }
@@ -139,14 +145,14 @@ void launch_mfma_dw(const void* G, int32_t Vp, const void* HcT, int32_t n_cp, in
         if ((size_t)tail * parts * CfgBig::BM * CfgBig::BN * 4 > mfma_dw_partial_bytes()) parts = 1;
     }
     if (parts < 2) {
-        launch<CfgBig, A_BLK_KM, WG_RANGES>(G, Vp, HcT, n_cp, V, D, n_cp, e, st);
+        launch<CfgGrad, A_BLK_KM, WG_RANGES>(G, Vp, HcT, n_cp, V, D, n_cp, e, st);
         return;
     }
-    launch<CfgBig, A_BLK_KM, WG_RANGES>(G, Vp, HcT, n_cp, V, D, n_cp, e, st, 0, tiles - tail, 1);
+    launch<CfgGrad, A_BLK_KM, WG_RANGES>(G, Vp, HcT, n_cp, V, D, n_cp, e, st, 0, tiles - tail, 1);
     EpiStoreDW ep = e;
     ep.partial = partial;
-    launch<CfgBig, A_BLK_KM, WG_RANGES>(G, Vp, HcT, n_cp, V, D, n_cp, ep, st, tiles - tail, tail, parts);
-    sum_partial_tiles_kernel<CfgBig><<<dim3(tail, CfgBig::BM / 16), 256, 0, st>>>(
+    launch<CfgGrad, A_BLK_KM, WG_RANGES>(G, Vp, HcT, n_cp, V, D, n_cp, ep, st, tiles - tail, tail, parts);
+    sum_partial_tiles_kernel<CfgGrad><<<dim3(tail, CfgBig::BM / 16), 256, 0, st>>>(
         partial, tiles - tail, parts, tiles_m, tiles_n, reinterpret_cast<float*>(out.C), out.ldc, V, D, out.accumulate);
 }
 
