@@ -178,8 +178,8 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
     // shares that XCD's L2 at any time is one compact block of the tile walk.
     // WG_RANGES: every XCD gets one contiguous range of items (round boundaries then fall
     // anywhere in the bands, but consecutive rounds of an XCD are neighbours in the walk).
-    // Measured L2 misses per launch, rounds against ranges: dH 52 against 60 GB (3 % faster),
-    // vocabulary GEMM 38 against 45 GB, dW 55 against 47 GB (0.5 % slower): dW uses ranges.
+    // The vocabulary GEMM (bands of 4 x 126 tiles) uses rounds: 38 against 45 GB of L2 misses per
+    // launch. dH and dW (one-row bands of 10 tiles) use ranges.
     const int total = gridDim.x;
     int logical = blockIdx.x;
     {
