@@ -118,10 +118,33 @@ void layout(const dppo_head_shape& s, bool bwd, int32_t n_cp, WsPlan& p) {
     p.total = off;
 }
 
-int32_t target_chunk(int64_t N) {
+// Chunk size for N loss tokens: balanced chunks of at most CHUNK_MAX tokens, their number chosen so
+// that the dH GEMM (tiles of 256 tokens x 256 columns, one workgroup per compute unit, so it runs in
+// rounds of CHIP_CUS tiles) wastes little of its last round. Cost of a chunk in dH rounds: whole
+// rounds, plus the last one (a fraction if it is at most half full, since its tiles are then cut
+// along K), plus what every chunk costs regardless of its size (the dW read-modify-write, the
+// small kernels, ramps).
+constexpr int64_t CHIP_CUS = 256;         // MI355X
+constexpr double CHUNK_OVERHEAD_ROUNDS = 0.35;
+int32_t target_chunk(int64_t N, int32_t D) {
     if (N <= 0) return CHUNK_ALIGN;
-    const int64_t n_chunks = ceil_div(N, CHUNK_MAX);
-    return round_up32(ceil_div(N, n_chunks), CHUNK_ALIGN);
+    const int64_t tiles_n = ceil_div(D, 256);
+    const int64_t c0 = ceil_div(N, CHUNK_MAX);
+    double best = 0.0;
+    int64_t best_c = c0;
+    for (int64_t c = c0; c <= c0 + 6; ++c) {
+        const int64_t tiles = ceil_div(ceil_div(N, c), 256) * tiles_n;
+        const int64_t full = tiles / CHIP_CUS, tail = tiles % CHIP_CUS;
+        double rounds = (double)full;
+        if (tail > 0) {
+            int64_t parts = 2 * tail <= CHIP_CUS ? CHIP_CUS / tail : 1;
+            if (parts > 8) parts = 8;
+            rounds += 1.0 / (double)parts;
+        }
+        const double cost = (double)c * (rounds + CHUNK_OVERHEAD_ROUNDS);
+        if (c == c0 || cost < best) { best = cost; best_c = c; }
+    }
+    return round_up32(ceil_div(N, best_c), CHUNK_ALIGN);
 }
 
 int validate_shape(const dppo_head_shape* s) {
@@ -136,7 +159,7 @@ int validate_shape(const dppo_head_shape* s) {
 
 // Picks the largest chunk that fits `ws_bytes` (at most the balanced target chunk).
 int plan_for(const dppo_head_shape& s, bool bwd, size_t ws_bytes, WsPlan& p) {
-    const int32_t target = target_chunk(s.N);
+    const int32_t target = target_chunk(s.N, s.D);
     layout(s, bwd, target, p);
     if (p.total > ws_bytes) {
         WsPlan q;
@@ -338,7 +361,7 @@ int dppo_timing_read(double* ms, int64_t* launches, int reset) {
 size_t dppo_workspace_bytes(const dppo_head_shape* shape, int want_backward) {
     if (validate_shape(shape) != DPPO_OK) return 0;
     WsPlan p;
-    layout(*shape, want_backward != 0, target_chunk(shape->N), p);
+    layout(*shape, want_backward != 0, target_chunk(shape->N, shape->D), p);
     return p.total;
 }
 
@@ -484,7 +507,7 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
         if (s.dtype == 1) {
             {
                 StageTimer tm(DPPO_STAGE_DH_GEMM, st);
-                launch_mfma_dh(G, p.Vp, w + p.o_wt, cv.n_c, s.D, row_scale, oh, st);
+                launch_mfma_dh(G, p.Vp, w + p.o_wt, cv.n_c, s.D, row_scale, oh, reinterpret_cast<float*>(w + p.o_dwpart), st);
             }
             {
                 StageTimer tm(DPPO_STAGE_DW_GEMM, st);

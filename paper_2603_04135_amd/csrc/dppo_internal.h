@@ -151,9 +151,9 @@ int launch_mfma_logits_grad(const void* W, int32_t V, int32_t D, const void* Hc,
                             const int32_t* y, const float* lse, const float* c, void* G, int64_t ldg,
                             int32_t Vp, hipStream_t st);
 // dH rows of a chunk: C[n_c, D] = diag(row_scale) G[n_c, Vp] WT[D, Vp]^T with G in the blocked chunk
-// layout (pitch Vp); row_scale may be NULL (= 1).
+// layout (pitch Vp); row_scale may be NULL (= 1). `partial`: as for launch_mfma_dw.
 void launch_mfma_dh(const void* G, int32_t Vp, const void* WT, int32_t n_c, int32_t D, const float* row_scale,
-                    const StoreSpec& out, hipStream_t st);
+                    const StoreSpec& out, float* partial, hipStream_t st);
 // dW of a chunk: C[V, D] (+)= G^T HcT^T = sum_n G[n, v] HcT[d, n], G read k-major from the same blocks.
 // `partial` is scratch of mfma_dw_partial_bytes() bytes (or NULL): with it, the tiles of a
 // sparsely filled last round are split along K over the idle compute units.

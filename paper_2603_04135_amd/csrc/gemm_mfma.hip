@@ -40,10 +40,14 @@ void launch(const void* A, int64_t lda, const void* B, int64_t ldb, int M, int N
 
 // Sums the k_parts partial tiles of each of the n_tiles tiles from tile0 on, in part order, into
 // C (overwrite or accumulate). One workgroup per 16 rows of a tile; N and ldc multiples of 4.
+// With Cb != NULL the sums go out as bf16 instead: row m times row_scale[m] (if not NULL) to row
+// row_map[row_base + m] (if not NULL) of Cb.
 template <class Cfg>
 __global__ __launch_bounds__(256) void sum_partial_tiles_kernel(const float* __restrict__ partial, int tile0,
                                                                 int k_parts, int tiles_m, int tiles_n, float* C,
-                                                                int64_t ldc, int M, int N, int accumulate) {
+                                                                int64_t ldc, int M, int N, int accumulate,
+                                                                uint16_t* Cb, const int32_t* __restrict__ row_map,
+                                                                int64_t row_base, const float* __restrict__ row_scale) {
     typedef float f32x4v __attribute__((ext_vector_type(4)));
     constexpr int VPR = Cfg::BN / 4;
     int tm, tn;
@@ -56,6 +60,15 @@ __global__ __launch_bounds__(256) void sum_partial_tiles_kernel(const float* __r
         f32x4v v = *reinterpret_cast<const f32x4v*>(src + (size_t)r * Cfg::BN + cv * 4);
         for (int p = 1; p < k_parts; ++p)
             v += *reinterpret_cast<const f32x4v*>(src + (size_t)p * (Cfg::BM * Cfg::BN) + (size_t)r * Cfg::BN + cv * 4);
+        if (Cb) {
+            const float rs = row_scale ? row_scale[row] : 1.0f;
+            const int64_t orow = row_map ? (int64_t)row_map[row_base + row] : (int64_t)row;
+            const __bf16 b0 = (__bf16)(v[0] * rs), b1 = (__bf16)(v[1] * rs), b2 = (__bf16)(v[2] * rs), b3 = (__bf16)(v[3] * rs);
+            const uint32_t lo = (uint32_t)__builtin_bit_cast(uint16_t, b0) | ((uint32_t)__builtin_bit_cast(uint16_t, b1) << 16);
+            const uint32_t hi = (uint32_t)__builtin_bit_cast(uint16_t, b2) | ((uint32_t)__builtin_bit_cast(uint16_t, b3) << 16);
+            *reinterpret_cast<uint2*>(Cb + (size_t)orow * ldc + col) = make_uint2(lo, hi);
+            continue;
+        }
         f32x4v* dst = reinterpret_cast<f32x4v*>(C + (size_t)row * ldc + col);
         if (accumulate) v += *dst;
         *dst = v;
@@ -119,33 +132,54 @@ int launch_mfma_logits_grad(const void* W, int32_t V, int32_t D, const void* Hc,
     return DPPO_OK;
 }
 
-void launch_mfma_dh(const void* G, int32_t Vp, const void* WT, int32_t n_c, int32_t D, const float* row_scale,
-                    const StoreSpec& out, hipStream_t st) {
-    EpiStoreDH e{nullptr, reinterpret_cast<uint16_t*>(out.C), out.ldc, 0, out.row_map, out.row_base, row_scale, nullptr};
-    launch<CfgGrad, A_BLK_ROWS, WG_RANGES>(G, Vp, WT, Vp, n_c, D, Vp, e, st);
-}
-
 size_t mfma_dw_partial_bytes() { return (size_t)256 * CfgBig::BM * CfgBig::BN * 4; }
 
-void launch_mfma_dw(const void* G, int32_t Vp, const void* HcT, int32_t n_cp, int32_t V, int32_t D,
-                    const StoreSpec& out, float* partial, hipStream_t st) {
-    EpiStoreDW e{reinterpret_cast<float*>(out.C), nullptr, out.ldc, out.accumulate, nullptr, 0, nullptr, nullptr};
-    const int tiles_m = (int)ceil_div(V, CfgBig::BM), tiles_n = (int)ceil_div(D, CfgBig::BN);
-    const int tiles = tiles_m * tiles_n, cus = g_compute_units;
-    // One workgroup per compute unit at a time: the last round of tiles holds tiles % cus of them.
-    // If that is at most half the chip, those tiles are cut along K into as many parts as fill it,
-    // each part writes its partial tile to scratch, and a small kernel adds the parts up in order
-    // (the same sums in a different association; deterministic).
-    const int tail = cus > 0 ? tiles % cus : 0;
+// One workgroup per compute unit at a time: the last round of tiles holds tiles % cus of them. If
+// that is at most half the chip, those tiles are cut along K into as many parts as fill it (at
+// most 8, at least 16 slices each), each part writes its partial tile to scratch, and a small
+// kernel adds the parts up in order (the same sums in a different association; deterministic).
+// Returns the number of parts (1 = no split) and the number of tail tiles.
+static int tail_split(int tiles, int k_slices, const float* partial, int& tail) {
+    const int cus = g_compute_units;
+    tail = cus > 0 ? tiles % cus : 0;
     int parts = 1;
     if (partial && tail > 0 && 2 * tail <= cus) {
         parts = cus / tail;
         if (parts > 8) parts = 8;
-        const int kt = n_cp / CfgBig::BK;
-        if (parts > kt / 16) parts = kt / 16;          // at least 16 slices per part
+        if (parts > k_slices / 16) parts = k_slices / 16;
         if ((size_t)tail * parts * CfgBig::BM * CfgBig::BN * 4 > mfma_dw_partial_bytes()) parts = 1;
     }
-    if (parts < 2) {
+    return parts < 2 ? 1 : parts;
+}
+
+void launch_mfma_dh(const void* G, int32_t Vp, const void* WT, int32_t n_c, int32_t D, const float* row_scale,
+                    const StoreSpec& out, float* partial, hipStream_t st) {
+    EpiStoreDH e{nullptr, reinterpret_cast<uint16_t*>(out.C), out.ldc, 0, out.row_map, out.row_base, row_scale, nullptr};
+    const int tiles_m = (int)ceil_div(n_c, CfgGrad::BM), tiles_n = (int)ceil_div(D, CfgGrad::BN);
+    const int tiles = tiles_m * tiles_n;
+    int tail;
+    const int parts = tail_split(tiles, Vp / CfgGrad::BK, partial, tail);
+    if (parts == 1) {
+        launch<CfgGrad, A_BLK_ROWS, WG_RANGES>(G, Vp, WT, Vp, n_c, D, Vp, e, st);
+        return;
+    }
+    launch<CfgGrad, A_BLK_ROWS, WG_RANGES>(G, Vp, WT, Vp, n_c, D, Vp, e, st, 0, tiles - tail, 1);
+    EpiStoreDH ep = e;
+    ep.partial = partial;
+    launch<CfgGrad, A_BLK_ROWS, WG_RANGES>(G, Vp, WT, Vp, n_c, D, Vp, ep, st, tiles - tail, tail, parts);
+    sum_partial_tiles_kernel<CfgGrad><<<dim3(tail, CfgGrad::BM / 16), 256, 0, st>>>(
+        partial, tiles - tail, parts, tiles_m, tiles_n, nullptr, out.ldc, n_c, D, 0, reinterpret_cast<uint16_t*>(out.C),
+        out.row_map, out.row_base, row_scale);
+}
+
+void launch_mfma_dw(const void* G, int32_t Vp, const void* HcT, int32_t n_cp, int32_t V, int32_t D,
+                    const StoreSpec& out, float* partial, hipStream_t st) {
+    EpiStoreDW e{reinterpret_cast<float*>(out.C), nullptr, out.ldc, out.accumulate, nullptr, 0, nullptr, nullptr};
+    const int tiles_m = (int)ceil_div(V, CfgGrad::BM), tiles_n = (int)ceil_div(D, CfgGrad::BN);
+    const int tiles = tiles_m * tiles_n;
+    int tail;
+    const int parts = tail_split(tiles, n_cp / CfgGrad::BK, partial, tail);
+    if (parts == 1) {
         launch<CfgGrad, A_BLK_KM, WG_RANGES>(G, Vp, HcT, n_cp, V, D, n_cp, e, st);
         return;
     }
@@ -153,8 +187,9 @@ void launch_mfma_dw(const void* G, int32_t Vp, const void* HcT, int32_t n_cp, in
     EpiStoreDW ep = e;
     ep.partial = partial;
     launch<CfgGrad, A_BLK_KM, WG_RANGES>(G, Vp, HcT, n_cp, V, D, n_cp, ep, st, tiles - tail, tail, parts);
-    sum_partial_tiles_kernel<CfgGrad><<<dim3(tail, CfgBig::BM / 16), 256, 0, st>>>(
-        partial, tiles - tail, parts, tiles_m, tiles_n, reinterpret_cast<float*>(out.C), out.ldc, V, D, out.accumulate);
+    sum_partial_tiles_kernel<CfgGrad><<<dim3(tail, CfgGrad::BM / 16), 256, 0, st>>>(
+        partial, tiles - tail, parts, tiles_m, tiles_n, reinterpret_cast<float*>(out.C), out.ldc, V, D, out.accumulate,
+        nullptr, nullptr, 0, nullptr);
 }
 
 }  // namespace dppo

@@ -417,7 +417,7 @@ template <int KIND>
 struct EpiStore {
     float* Cf; uint16_t* Cb; int64_t ldc; int accumulate; const int32_t* row_map; int64_t row_base;
     const float* row_scale;   // KIND 1: output row m is multiplied by row_scale[m] if not NULL
-    float* partial;           // KIND 0: if not NULL, work item i stores its whole BM x BN tile, row-major, at
+    float* partial;           // if not NULL, work item i stores its whole BM x BN fp32 tile, row-major, at
                               // partial + i * BM * BN instead (launches that split K; summed up by a second kernel)
 
     template <class Cfg>
@@ -462,6 +462,19 @@ struct EpiStore {
                 }
                 __syncthreads();
             }
+            return;
+        }
+        if (partial) {       // K-split launch: the raw fp32 tile, row-major, to this work item's slot
+            float* dst = partial + (size_t)c.item * (Cfg::BM * Cfg::BN);
+#pragma unroll
+            for (int mi = 0; mi < Cfg::MI; ++mi)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int r = c.wave_m * Cfg::WTM + mi * MB + acc_row(c.lane, j);
+#pragma unroll
+                    for (int ni = 0; ni < Cfg::NI; ++ni)
+                        dst[(size_t)r * Cfg::BN + c.wave_n * Cfg::WTN + ni * MB + acc_col(c.lane)] = acc[mi][ni][j];
+                }
             return;
         }
 #pragma unroll

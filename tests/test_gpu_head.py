@@ -39,6 +39,13 @@ def _same_loss(a, b, ref_out, case):
     return _loss_close(float(a), dict(ref_out, loss=float(b)), case, 1e-5)
 
 
+def _same_rows(a, b):
+    """dH of two chunkings of the same batch: the same fp32 sums, possibly associated differently
+    (the tiles of a sparsely filled last round are summed in K-split parts), then rounded to bf16."""
+    a64, b64 = to_np64(a), to_np64(b)
+    return rel_fro(a64, b64) <= 1e-3 and float((a64 == b64).mean()) >= 0.98
+
+
 def _run_case(P, case, tol, **kw):
     """Full parity of one case: log-probs, loss, per-sequence loss, stats, dH, dW."""
     logp_ref, lse_ref = case.oracle_logprob()
@@ -178,7 +185,7 @@ def test_objective_variants(lib, ratio_level, aggregation):
             case.logp_ref)
     kw = dict(beta=0.04, ratio_level=ratio_level, aggregation=aggregation, **clip)
     small = lib.dppo_loss_fwd_bwd(*args, ws=lib.alloc_workspace((ws_min + ws_full) // 2, DEV), **kw)
-    assert torch.equal(small["dH"], out["dH"]) and torch.equal(small["seq_loss"], out["seq_loss"])
+    assert _same_rows(small["dH"], out["dH"]) and torch.equal(small["seq_loss"], out["seq_loss"])
     rec = lib.dppo_loss_fwd_bwd(*args, recompute_logits=True, **kw)
     assert rel_fro(to_np64(rec["dW"]), ref["dW"]) <= 1e-2 and _same_loss(rec["loss"], out["loss"], ref, case)
 
@@ -247,7 +254,7 @@ def test_identity_rows_chunking_accumulation_and_recompute(lib):
     chunked = P.dppo_loss_fwd_bwd(*args, ws=small_ws)
     assert rel_fro(to_np64(chunked["dW"]), ref["dW"]) <= 1e-2
     assert rel_fro(to_np64(chunked["dW"]), to_np64(base["dW"])) <= 1e-4
-    assert torch.equal(chunked["dH"], base["dH"])
+    assert _same_rows(chunked["dH"], base["dH"])
     assert abs(float(chunked["loss"]) - float(base["loss"])) <= 1e-6 * abs(float(base["loss"])) + 1e-9
     # (b) accumulate_dW adds to the buffer
     acc = base["dW"].clone()
