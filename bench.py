@@ -25,8 +25,9 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak
 # (workload, kernel, recompute); an entry is deleted when that kernel changes, until the counters
 # are taken again.
 MEASURED_TRAFFIC_BYTES = {
-    ("qwen3_4b", "logits_gemm", False): 2.0 * 19257695 * 1024 + 9730194 * 1024,
-    ("qwen3_4b", "dw_gemm", False): 2.0 * (21966873 + 29426) * 1024 + (1560576 + 12032) * 1024,   # both dispatches + the sum
+    ("qwen3_4b", "logits_gemm", False): 2.0 * 18858430 * 1024 + 9730179 * 1024,
+    ("qwen3_4b", "dh_gemm", False): 2.0 * 21368820 * 1024 + 161168 * 1024,
+    ("qwen3_4b", "dw_gemm", False): 2.0 * (21963849 + 29430) * 1024 + (1560576 + 12032) * 1024,   # both dispatches + the sum
 }
 
 
