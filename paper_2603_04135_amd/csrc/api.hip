@@ -79,6 +79,11 @@ struct WsPlan {
 
 int32_t round_up32(int64_t x, int32_t a) { return (int32_t)((x + a - 1) / a * a); }
 
+// Row pitch (elements) of the transposed hidden-state chunk HcT[D, n_cp] of the bf16 path: a pitch
+// that is a multiple of 4 KB sends all rows of a k-slice to the same few L2 channels (the dW GEMM
+// reads 256 such rows per slice), so such chunk sizes get 64 elements of padding per row.
+int64_t hct_pitch(int dtype, int32_t n_cp) { return dtype == 1 && n_cp % 2048 == 0 ? (int64_t)n_cp + 64 : (int64_t)n_cp; }
+
 // Lays the workspace out for chunk size n_cp (multiple of CHUNK_ALIGN).
 void layout(const dppo_head_shape& s, bool bwd, int32_t n_cp, WsPlan& p) {
     p.es = s.dtype == 1 ? 2 : 4;
@@ -100,7 +105,7 @@ void layout(const dppo_head_shape& s, bool bwd, int32_t n_cp, WsPlan& p) {
     p.o_dwpart = take(bwd && s.dtype == 1 ? mfma_dw_partial_bytes() : 0);
     p.fixed_bytes = off;
     p.o_hc = take((size_t)n_cp * s.D * p.es);
-    p.o_hct = take(bwd ? (size_t)n_cp * s.D * p.es : 0);
+    p.o_hct = take(bwd ? (size_t)(n_cp + 64) * s.D * p.es : 0);   // room for hct_pitch of any chunk
     p.o_part = take((size_t)p.n_tiles * n_cp * 8);
     p.o_zg = take(need_z ? (size_t)n_cp * p.Vp * p.zs : 0);
     p.o_gt = take(bwd && s.dtype == 0 ? (size_t)n_cp * p.Vp * p.zs : 0);   // transposed copy: float32 path only
@@ -493,7 +498,8 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
                                  lse_c, ta.c_chunk, cv, G, p.Vp, scale, st);
             row_scale = scale;
         }
-        if (s.dtype == 1) launch_scale_transpose_bf16(w + p.o_hc, row_scale, cv.n_cp, s.D, w + p.o_hct, st);
+        if (s.dtype == 1)
+            launch_scale_transpose_bf16(w + p.o_hc, row_scale, cv.n_cp, s.D, w + p.o_hct, hct_pitch(1, cv.n_cp), st);
 
         // dH rows of the chunk: diag(row_scale) G[n_c, Vp] * WT[D, Vp]^T, scattered to the loss rows of dH
         StoreSpec oh;
@@ -511,7 +517,8 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
             }
             {
                 StageTimer tm(DPPO_STAGE_DW_GEMM, st);
-                launch_mfma_dw(G, p.Vp, w + p.o_hct, cv.n_cp, s.V, s.D, ow, reinterpret_cast<float*>(w + p.o_dwpart), st);
+                launch_mfma_dw(G, p.Vp, w + p.o_hct, hct_pitch(1, cv.n_cp), cv.n_cp, s.V, s.D, ow,
+                               reinterpret_cast<float*>(w + p.o_dwpart), st);
             }
         } else {
             launch_gemm_plain_f32(reinterpret_cast<const float*>(G), p.Vp, reinterpret_cast<const float*>(w + p.o_wt),

@@ -75,9 +75,10 @@ void launch_exp_redo_rows(const int32_t* redo_count, const int32_t* redo_list, f
 // scale[n] E[n, v] = c[n] (1[v == y[n]] - softmax[n, v]).
 void launch_softmax_scale(const int32_t* y, const float* zy, const float* bref, const float* lse, const float* c,
                           ChunkView cv, void* E, int64_t lde, float* scale, hipStream_t st);
-// HcT[D, n_cp] = transpose of diag(scale) Hc[n_cp, D] in bf16 (scale NULL = 1).
+// HcT[D, n_cp] (row pitch ld_hct >= n_cp elements, a multiple of 8) = transpose of
+// diag(scale) Hc[n_cp, D] in bf16 (scale NULL = 1).
 void launch_scale_transpose_bf16(const void* Hc, const float* scale, int32_t n_cp, int32_t D, void* HcT,
-                                 hipStream_t st);
+                                 int64_t ld_hct, hipStream_t st);
 // fp32 path: row statistics straight from stored logits Z[n_cp, ldz].
 void launch_row_stats_f32(const float* Z, int64_t ldz, int32_t V, const int32_t* y, ChunkView cv,
                           float* lse_chunk, float* logp_out, float* lse_out, hipStream_t st);
@@ -154,11 +155,12 @@ int launch_mfma_logits_grad(const void* W, int32_t V, int32_t D, const void* Hc,
 // layout (pitch Vp); row_scale may be NULL (= 1). `partial`: as for launch_mfma_dw.
 void launch_mfma_dh(const void* G, int32_t Vp, const void* WT, int32_t n_c, int32_t D, const float* row_scale,
                     const StoreSpec& out, float* partial, hipStream_t st);
-// dW of a chunk: C[V, D] (+)= G^T HcT^T = sum_n G[n, v] HcT[d, n], G read k-major from the same blocks.
+// dW of a chunk: C[V, D] (+)= G^T HcT^T = sum_n G[n, v] HcT[d, n] (HcT row pitch ld_hct), G read k-major from the
+// same blocks.
 // `partial` is scratch of mfma_dw_partial_bytes() bytes (or NULL): with it, the tiles of a
 // sparsely filled last round are split along K over the idle compute units.
 size_t mfma_dw_partial_bytes();
-void launch_mfma_dw(const void* G, int32_t Vp, const void* HcT, int32_t n_cp, int32_t V, int32_t D,
+void launch_mfma_dw(const void* G, int32_t Vp, const void* HcT, int64_t ld_hct, int32_t n_cp, int32_t V, int32_t D,
                     const StoreSpec& out, float* partial, hipStream_t st);
 
 }  // namespace dppo

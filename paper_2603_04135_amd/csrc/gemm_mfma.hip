@@ -172,7 +172,7 @@ void launch_mfma_dh(const void* G, int32_t Vp, const void* WT, int32_t n_c, int3
         out.row_map, out.row_base, row_scale);
 }
 
-void launch_mfma_dw(const void* G, int32_t Vp, const void* HcT, int32_t n_cp, int32_t V, int32_t D,
+void launch_mfma_dw(const void* G, int32_t Vp, const void* HcT, int64_t ld_hct, int32_t n_cp, int32_t V, int32_t D,
                     const StoreSpec& out, float* partial, hipStream_t st) {
     EpiStoreDW e{reinterpret_cast<float*>(out.C), nullptr, out.ldc, out.accumulate, nullptr, 0, nullptr, nullptr};
     const int tiles_m = (int)ceil_div(V, CfgGrad::BM), tiles_n = (int)ceil_div(D, CfgGrad::BN);
@@ -180,13 +180,13 @@ void launch_mfma_dw(const void* G, int32_t Vp, const void* HcT, int32_t n_cp, in
     int tail;
     const int parts = tail_split(tiles, n_cp / CfgGrad::BK, partial, tail);
     if (parts == 1) {
-        launch<CfgGrad, A_BLK_KM, WG_RANGES>(G, Vp, HcT, n_cp, V, D, n_cp, e, st);
+        launch<CfgGrad, A_BLK_KM, WG_RANGES>(G, Vp, HcT, ld_hct, V, D, n_cp, e, st);
         return;
     }
-    launch<CfgGrad, A_BLK_KM, WG_RANGES>(G, Vp, HcT, n_cp, V, D, n_cp, e, st, 0, tiles - tail, 1);
+    launch<CfgGrad, A_BLK_KM, WG_RANGES>(G, Vp, HcT, ld_hct, V, D, n_cp, e, st, 0, tiles - tail, 1);
     EpiStoreDW ep = e;
     ep.partial = partial;
-    launch<CfgGrad, A_BLK_KM, WG_RANGES>(G, Vp, HcT, n_cp, V, D, n_cp, ep, st, tiles - tail, tail, parts);
+    launch<CfgGrad, A_BLK_KM, WG_RANGES>(G, Vp, HcT, ld_hct, V, D, n_cp, ep, st, tiles - tail, tail, parts);
     sum_partial_tiles_kernel<CfgGrad><<<dim3(tail, CfgGrad::BM / 16), 256, 0, st>>>(
         partial, tiles - tail, parts, tiles_m, tiles_n, reinterpret_cast<float*>(out.C), out.ldc, V, D, out.accumulate,
         nullptr, nullptr, 0, nullptr);

@@ -644,10 +644,10 @@ void launch_softmax_scale(const int32_t* y, const float* zy, const float* bref, 
 }
 
 void launch_scale_transpose_bf16(const void* Hc, const float* scale, int32_t n_cp, int32_t D, void* HcT,
-                                 hipStream_t st) {
+                                 int64_t ld_hct, hipStream_t st) {
     dim3 grid((unsigned)(D / 64), (unsigned)(n_cp / 64));
     transpose_bf16_kernel<<<grid, 256, 0, st>>>(reinterpret_cast<const uint16_t*>(Hc), D, n_cp, scale,
-                                                reinterpret_cast<uint16_t*>(HcT), n_cp);
+                                                reinterpret_cast<uint16_t*>(HcT), ld_hct);
 }
 
 void launch_combine_logprob(const float2* part, int32_t n_tiles, const float* zy, ChunkView cv, float* lse_chunk,

@@ -128,6 +128,10 @@ def test_long_chunk_with_few_output_tiles(lib):
     lib.dppo_loss_fwd_bwd(case.H, case.W, case.ids, case.loss_pos, case.loss_cu, case.seq_adv, case.seq_coef,
                           case.logp_old, case.logp_ref, dW=acc, accumulate_dW=True)
     assert torch.equal(acc, 2.0 * out["dW"])
+    # a chunk of exactly 2048 tokens: the transposed hidden-state chunk gets a padded row pitch
+    case = _case("small", 2048, dtype="bf16", D=256, V=2000)
+    assert case.pk["N"] == 2048
+    _run_case(lib, case, TOL["bf16"])
 
 
 def test_clipping_zero_advantage_and_single_token_sequences(lib):
