@@ -8,12 +8,16 @@
  *     allocates or frees device memory (scratch is the caller's `ws`);
  *   - parameter structs and the returned status live on the host;
  *   - calls are asynchronous on `stream` (a hipStream_t passed as void*, NULL = the
- *     default stream) and never synchronise it;
+ *     default stream) and never synchronise it (the one exception is the benchmark aid
+ *     dppo_timing_read, which waits for its events on the host);
  *   - arguments that can be checked on the host (NULL pointers, non-positive sizes,
  *     rates outside [0,1), too small a workspace) are checked before anything is
  *     launched: the call returns an error status and launches nothing;
  *   - conditions only the device can see are reported through a device-side status
- *     word (see dppo_pack) and leave the outputs defined;
+ *     word (dppo_pack: meta[3]; the LM-head calls: `status`) and leave the outputs defined;
+ *   - the library keeps no state between calls except: the message of the last error
+ *     (per thread), per-device kernel attributes and compute-unit count (looked up on the
+ *     first bfloat16 LM-head call on each device), and the optional stage timing below;
  *   - no C++ exception crosses this boundary.
  */
 #ifndef DPPO_H_
@@ -68,7 +72,8 @@ const char* dppo_last_error(void);
  * Layout: rewards, u_comp, adv, keep_comp, gamma_o, coef are [Q*G] row-major (prompt
  * major); hist, u_prompt, mean_abs_adv, keep_prompt, gamma_q are [Q]; counts is [1+Q].
  * Masks are bit-exact functions of the inputs. Requires Q <= 16384, G <= 1024,
- * G - std_ddof >= 1, r_q and r_o in [0,1), 0 <= bottom_frac <= 1.
+ * G - std_ddof >= 1, r_q and r_o in [0,1), 0 <= bottom_frac <= 1, adv_eps > 0 (a group of
+ * equal rewards has standard deviation 0; with adv_eps > 0 its advantages are 0).
  */
 typedef struct {
     int32_t Q, G;
@@ -123,8 +128,9 @@ int dppo_history_update(int32_t n, const int32_t* prompt_index, const uint8_t* k
  *   loss_cu[s]     first loss token of packed sequence s; [S] = N       [n_items+1]
  *   loss_pos[n]    packed position whose hidden state predicts the n-th completion token:
  *                  sequence s contributes cu[s]+P-1 ... cu[s]+P+C-2     [loss_pos_capacity]
- *   meta[8]        {n_rows, T, N, device_status, S, capacity used, 0, 0}; the share of row slots
- *                  that hold a real token (fill density) is T / (n_rows * capacity used)
+ *   meta[8]        {n_rows, T, N, device_status, S, capacity used, d_lo, d_hi}; d_lo, d_hi are the
+ *                  low and high 32 bits of a double: the fill density T / (n_rows * capacity
+ *                  used), the share of row slots that hold a real token (0 if nothing is packed)
  * device_status: 0 ok; 1 = a kept item has prompt_len < 1, comp_len < 1 or does not fit
  * `capacity`; 2 = N exceeds loss_pos_capacity; 3 = T does not fit int32. On a non-zero
  * status n_rows = T = N = S = 0 and no other output is meaningful.
@@ -159,7 +165,15 @@ int dppo_gather_f32(int64_t n, const int32_t* idx, const float* src, float* dst,
  * accumulation (needs D % 64 == 0). Statistics (max, sum-exp, log-probs, loss terms) are
  * fp32; logits are never written out in full (at most one token chunk at a time, in the
  * workspace).
+ * status (device int32, or NULL): cleared at the start of the call, then OR-ed with
+ *   DPPO_HEAD_BAD_TARGET    a target id outside [0,V): the id is clamped into the range;
+ *   DPPO_HEAD_BAD_POSITION  a loss_pos entry p with p < 0 or p + 1 >= T: the row and its target
+ *                           position are clamped into [0,T).
+ * Every kernel still runs to the end and every output is defined; what the outputs mean for the
+ * offending tokens is up to the caller. Entries of loss_pos must be distinct (not checked).
  */
+enum { DPPO_HEAD_BAD_TARGET = 1, DPPO_HEAD_BAD_POSITION = 2 };
+
 typedef struct {
     int64_t T, N;
     int32_t D, V;
@@ -176,11 +190,12 @@ size_t dppo_workspace_min_bytes(const dppo_head_shape* shape, int want_backward)
 int dppo_token_logprob(const dppo_head_shape* shape,
                        const void* H, const void* W, const int32_t* ids,
                        const int32_t* loss_pos /* or NULL */,
-                       float* logp, float* lse /* or NULL */,
+                       float* logp, float* lse /* or NULL */, int32_t* status /* or NULL */,
                        void* ws, size_t ws_bytes, void* stream);
 
 /* Loss L = sum_s seq_coef[s] * (1/C_s) * sum_{n in s} l_n over the S packed sequences
- * (segments loss_cu[s]..loss_cu[s+1] of the loss tokens, C_s their length), with
+ * (segments loss_cu[s]..loss_cu[s+1] of the loss tokens, C_s their length; loss_cu must be
+ * non-decreasing from 0 to N, and an empty segment contributes 0, with seq_loss[s] = 0), with
  *   rho = exp(logp - logp_old),  l = -min(rho A, clip(rho, 1-clip_lo, 1+clip_hi) A)
  *   + beta (rho_hat - log rho_hat - 1),  rho_hat = exp(logp_ref - logp),  A = seq_adv[s]
  * (Eq. 1; the weight multiplies surrogate and KL alike), and its gradients
@@ -224,7 +239,7 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* p, i
                       const float* seq_adv, const float* seq_coef,
                       const float* logp_old, const float* logp_ref,
                       float* loss, float* logp /* or NULL */, float* seq_loss /* or NULL */,
-                      float* stats /* or NULL */,
+                      float* stats /* or NULL */, int32_t* status /* or NULL */,
                       void* dH, float* dW,
                       void* ws, size_t ws_bytes, void* stream);
 
@@ -253,6 +268,8 @@ int dppo_token_norm_coef(int32_t Q, int32_t G, const int32_t* comp_len, const fl
  * the caller's stream (the kernels themselves are unchanged). dppo_timing_read waits for the
  * recorded events (a host-side wait), returns the summed milliseconds and the launch count
  * of every stage since the last reset, and with reset != 0 forgets them. Host arrays.
+ * The switch and the recorded events are process-wide state (guarded by a mutex). Events
+ * cannot be recorded on a stream that is being captured into a graph: keep timing off then.
  */
 enum {
     DPPO_STAGE_LOGITS_GEMM = 0, /* vocabulary GEMM with the online max / sum-exp epilogue */

@@ -52,6 +52,7 @@ class LossParams(ctypes.Structure):
                 ("ratio_level", c_int32), ("aggregation", c_int32)]
 
 
+HEAD_BAD_TARGET, HEAD_BAD_POSITION = 1, 2     # bits of the LM-head calls' device status word
 RATIO_LEVELS = {"token": 0, "sequence": 1}
 AGGREGATIONS = {"seq_mean": 0, "token_sum": 1}
 
@@ -88,9 +89,9 @@ def load():
     lib.dppo_workspace_min_bytes.restype = c_size_t
     lib.dppo_workspace_min_bytes.argtypes = [POINTER(HeadShape), c_int]
     lib.dppo_token_logprob.restype = c_int
-    lib.dppo_token_logprob.argtypes = [POINTER(HeadShape)] + [c_void_p] * 7 + [c_size_t, c_void_p]
+    lib.dppo_token_logprob.argtypes = [POINTER(HeadShape)] + [c_void_p] * 8 + [c_size_t, c_void_p]
     lib.dppo_loss_fwd_bwd.restype = c_int
-    lib.dppo_loss_fwd_bwd.argtypes = ([POINTER(HeadShape), POINTER(LossParams), c_int32] + [c_void_p] * 16
+    lib.dppo_loss_fwd_bwd.argtypes = ([POINTER(HeadShape), POINTER(LossParams), c_int32] + [c_void_p] * 17
                                       + [c_size_t, c_void_p])
     lib.dppo_history_update.restype = c_int
     lib.dppo_history_update.argtypes = [c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_void_p]
@@ -221,11 +222,13 @@ def dppo_pack(prompt_len, comp_len, keep, capacity: int, n_win: int, loss_pos_ca
     st = lib.dppo_pack(ctypes.byref(p), _ptr(prompt_len), _ptr(comp_len), _ptr(keep), _ptr(order), _ptr(row_ptr),
                        _ptr(cu), _ptr(lcu), _ptr(loss_pos), loss_pos_capacity, _ptr(meta), _stream(device))
     _check(st, "dppo_pack")
-    m = meta.cpu().tolist()
+    meta_host = meta.cpu()
+    m = meta_host.tolist()
     n_rows, T, N, dev_status, S, cap = m[0], m[1], m[2], m[3], m[4], m[5]
+    density = float(meta_host[6:8].view(torch.float64)[0])     # the library's own number (a double in two words)
     return dict(order=order[:S], row_ptr=row_ptr[:n_rows + 1], cu_seqlens=cu[:S + 1], loss_cu=lcu[:S + 1],
                 loss_pos=loss_pos[:N], n_rows=n_rows, T=T, N=N, S=S, device_status=dev_status, capacity=cap,
-                density=(T / (n_rows * cap)) if n_rows else 0.0)
+                density=density)
 
 
 def dppo_token_norm_coef(coef: torch.Tensor, comp_len) -> torch.Tensor:
@@ -273,8 +276,10 @@ def alloc_workspace(nbytes: int, device) -> torch.Tensor:
     return torch.empty(max(256, nbytes), dtype=torch.uint8, device=device)
 
 
-def dppo_token_logprob(H, W, ids, loss_pos=None, want_lse: bool = True, ws: Optional[torch.Tensor] = None):
-    """Returns (logp[N], lse[N] or None) as float32 device tensors."""
+def dppo_token_logprob(H, W, ids, loss_pos=None, want_lse: bool = True, ws: Optional[torch.Tensor] = None,
+                       status: Optional[torch.Tensor] = None):
+    """Returns (logp[N], lse[N] or None) as float32 device tensors. status: optional int32[1] device
+    tensor that receives the device-side status word (DPPO_HEAD_BAD_*)."""
     lib = load()
     device = H.device
     N = H.shape[0] if loss_pos is None else loss_pos.numel()
@@ -284,7 +289,7 @@ def dppo_token_logprob(H, W, ids, loss_pos=None, want_lse: bool = True, ws: Opti
     logp = torch.empty(N, dtype=torch.float32, device=device)
     lse = torch.empty(N, dtype=torch.float32, device=device) if want_lse else None
     st = lib.dppo_token_logprob(ctypes.byref(shape), _ptr(H), _ptr(W), _ptr(ids), _ptr(loss_pos), _ptr(logp),
-                                _ptr(lse), _ptr(ws), ws.numel(), _stream(device))
+                                _ptr(lse), _ptr(status), _ptr(ws), ws.numel(), _stream(device))
     _check(st, "dppo_token_logprob")
     return logp, lse
 
@@ -294,8 +299,10 @@ def dppo_loss_fwd_bwd(H, W, ids, loss_pos, loss_cu, seq_adv, seq_coef, logp_old,
                       dW: Optional[torch.Tensor] = None, accumulate_dW: bool = False,
                       recompute_logits: bool = False, ws: Optional[torch.Tensor] = None,
                       dH: Optional[torch.Tensor] = None, out: Optional[dict] = None,
-                      ratio_level: str = "token", aggregation: str = "seq_mean") -> dict:
-    """Returns dict(loss[1], logp[N], seq_loss[S], stats[4], dH[T,D], dW[V,D]) of device tensors."""
+                      ratio_level: str = "token", aggregation: str = "seq_mean",
+                      status: Optional[torch.Tensor] = None) -> dict:
+    """Returns dict(loss[1], logp[N], seq_loss[S], stats[4], dH[T,D], dW[V,D]) of device tensors.
+    status: optional int32[1] device tensor for the device-side status word (DPPO_HEAD_BAD_*)."""
     lib = load()
     device = H.device
     N = H.shape[0] if loss_pos is None else loss_pos.numel()
@@ -318,7 +325,7 @@ def dppo_loss_fwd_bwd(H, W, ids, loss_pos, loss_cu, seq_adv, seq_coef, logp_old,
     st = lib.dppo_loss_fwd_bwd(ctypes.byref(shape), ctypes.byref(p), S, _ptr(H), _ptr(W), _ptr(ids), _ptr(loss_pos),
                                _ptr(loss_cu), _ptr(seq_adv), _ptr(seq_coef), _ptr(logp_old), _ptr(logp_ref),
                                _ptr(out["loss"]), _ptr(out["logp"]), _ptr(out["seq_loss"]), _ptr(out["stats"]),
-                               _ptr(dH), _ptr(dW), _ptr(ws), ws.numel(), _stream(device))
+                               _ptr(status), _ptr(dH), _ptr(dW), _ptr(ws), ws.numel(), _stream(device))
     _check(st, "dppo_loss_fwd_bwd")
     res = dict(out)
     res["seq_loss"] = out["seq_loss"][:S]

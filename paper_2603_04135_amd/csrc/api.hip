@@ -72,7 +72,7 @@ struct WsPlan {
     size_t es, zs;                 // element sizes of H/W and of the stored logits / gradient entries
     size_t fixed_bytes, row_bytes; // bytes independent of / proportional to the chunk size
     // region offsets
-    size_t o_wt, o_logp, o_ell, o_kl, o_clip, o_seq, o_sratio, o_hc, o_hct, o_part, o_zg, o_gt, o_y, o_zy, o_lse, o_c;
+    size_t o_wt, o_logp, o_ell, o_kl, o_clip, o_seq, o_sratio, o_hc, o_hct, o_part, o_zg, o_gt, o_y, o_rowc, o_zy, o_lse, o_c;
     size_t o_bref, o_mx, o_scale, o_redo_list, o_redo_sum, o_redo_count, o_dwpart;   // bf16 backward only
     size_t total;
 };
@@ -110,6 +110,7 @@ void layout(const dppo_head_shape& s, bool bwd, int32_t n_cp, WsPlan& p) {
     p.o_zg = take(need_z ? (size_t)n_cp * p.Vp * p.zs : 0);
     p.o_gt = take(bwd && s.dtype == 0 ? (size_t)n_cp * p.Vp * p.zs : 0);   // transposed copy: float32 path only
     p.o_y = take((size_t)n_cp * 4);
+    p.o_rowc = take((size_t)n_cp * 4);
     p.o_zy = take((size_t)n_cp * 4);
     p.o_lse = take((size_t)n_cp * 4);
     p.o_c = take((size_t)n_cp * 4);
@@ -125,14 +126,15 @@ void layout(const dppo_head_shape& s, bool bwd, int32_t n_cp, WsPlan& p) {
 
 // Chunk size for N loss tokens: balanced chunks of at most CHUNK_MAX tokens, their number chosen so
 // that the dH GEMM (tiles of 256 tokens x 256 columns, one workgroup per compute unit, so it runs in
-// rounds of CHIP_CUS tiles) wastes little of its last round. Cost of a chunk in dH rounds: whole
+// rounds of one tile per compute unit) wastes little of its last round. Cost of a chunk in dH rounds: whole
 // rounds, plus the last one (a fraction if it is at most half full, since its tiles are then cut
 // along K), plus what every chunk costs regardless of its size (the dW read-modify-write, the
 // small kernels, ramps).
-constexpr int64_t CHIP_CUS = 256;         // MI355X
+constexpr int DEFAULT_CUS = 256;          // MI355X; used where no device is at hand (size queries)
 constexpr double CHUNK_OVERHEAD_ROUNDS = 0.35;
-int32_t target_chunk(int64_t N, int32_t D) {
+int32_t target_chunk(int64_t N, int32_t D, int cus) {
     if (N <= 0) return CHUNK_ALIGN;
+    const int64_t CHIP_CUS = cus > 0 ? cus : DEFAULT_CUS;
     const int64_t tiles_n = ceil_div(D, 256);
     const int64_t c0 = ceil_div(N, CHUNK_MAX);
     double best = 0.0;
@@ -162,9 +164,18 @@ int validate_shape(const dppo_head_shape* s) {
     return DPPO_OK;
 }
 
+// Host-checkable part of the workspace test (needs no device): the smallest chunk must fit.
+int check_min_workspace(const dppo_head_shape& s, bool bwd, size_t ws_bytes) {
+    WsPlan q;
+    layout(s, bwd, CHUNK_ALIGN, q);
+    if (q.total > ws_bytes)
+        return fail(DPPO_ERR_WORKSPACE, "workspace of %zu bytes is below the minimum of %zu", ws_bytes, q.total);
+    return DPPO_OK;
+}
+
 // Picks the largest chunk that fits `ws_bytes` (at most the balanced target chunk).
-int plan_for(const dppo_head_shape& s, bool bwd, size_t ws_bytes, WsPlan& p) {
-    const int32_t target = target_chunk(s.N, s.D);
+int plan_for(const dppo_head_shape& s, bool bwd, size_t ws_bytes, int cus, WsPlan& p) {
+    const int32_t target = target_chunk(s.N, s.D, cus);
     layout(s, bwd, target, p);
     if (p.total > ws_bytes) {
         WsPlan q;
@@ -196,13 +207,13 @@ struct Regions {
 // HcT), or as bf16 exponentials against the per-token reference left in the bref region (bf16 path).
 int chunk_forward(const dppo_head_shape& s, const WsPlan& p, char* ws, const void* H, const void* W,
                    const int32_t* ids, const int32_t* loss_pos, ChunkView cv, bool keep_z,
-                   float* logp_all, float* lse_all, hipStream_t st) {
+                   float* logp_all, float* lse_all, int32_t* status, hipStream_t st) {
     void* Hc = ws + p.o_hc;
     int32_t* y = reinterpret_cast<int32_t*>(ws + p.o_y);
     float* zy = reinterpret_cast<float*>(ws + p.o_zy);
     float* lse_c = reinterpret_cast<float*>(ws + p.o_lse);
     launch_gather_rows(s.dtype, H, ids, loss_pos, s.T, s.D, s.V, cv, Hc, keep_z && s.dtype == 0 ? ws + p.o_hct : nullptr,
-                       y, st);
+                       y, reinterpret_cast<int32_t*>(ws + p.o_rowc), status, st);
     if (s.dtype == 1 && keep_z) {
         float2* part = reinterpret_cast<float2*>(ws + p.o_part);
         float* bref = reinterpret_cast<float*>(ws + p.o_bref);
@@ -274,7 +285,7 @@ int dppo_select(const dppo_select_params* p, const float* rewards, const float* 
     if (p->G - p->std_ddof < 1) return fail(DPPO_ERR_SHAPE, "G - std_ddof must be at least 1");
     if (!(p->r_q >= 0.0f && p->r_q < 1.0f) || !(p->r_o >= 0.0f && p->r_o < 1.0f))
         return fail(DPPO_ERR_INVALID_ARG, "prune probabilities must lie in [0,1) (r_q=%g r_o=%g)", p->r_q, p->r_o);
-    if (!(p->adv_eps >= 0.0f)) return fail(DPPO_ERR_INVALID_ARG, "adv_eps must be >= 0");
+    if (!(p->adv_eps > 0.0f)) return fail(DPPO_ERR_INVALID_ARG, "adv_eps must be > 0 (a constant group has standard deviation 0)");
     if (!(p->bottom_frac >= 0.0f && p->bottom_frac <= 1.0f)) return fail(DPPO_ERR_INVALID_ARG, "bottom_frac must lie in [0,1]");
     if ((p->fixed_count != 0 && p->fixed_count != 1) || (p->realised_rate != 0 && p->realised_rate != 1))
         return fail(DPPO_ERR_INVALID_ARG, "fixed_count and realised_rate must be 0 or 1");
@@ -366,7 +377,7 @@ int dppo_timing_read(double* ms, int64_t* launches, int reset) {
 size_t dppo_workspace_bytes(const dppo_head_shape* shape, int want_backward) {
     if (validate_shape(shape) != DPPO_OK) return 0;
     WsPlan p;
-    layout(*shape, want_backward != 0, target_chunk(shape->N, shape->D), p);
+    layout(*shape, want_backward != 0, target_chunk(shape->N, shape->D, DEFAULT_CUS), p);
     return p.total;
 }
 
@@ -378,7 +389,8 @@ size_t dppo_workspace_min_bytes(const dppo_head_shape* shape, int want_backward)
 }
 
 int dppo_token_logprob(const dppo_head_shape* shape, const void* H, const void* W, const int32_t* ids,
-                       const int32_t* loss_pos, float* logp, float* lse, void* ws, size_t ws_bytes, void* stream) {
+                       const int32_t* loss_pos, float* logp, float* lse, int32_t* status, void* ws, size_t ws_bytes,
+                       void* stream) {
     int rc = validate_shape(shape);
     if (rc != DPPO_OK) return rc;
     const dppo_head_shape& s = *shape;
@@ -386,18 +398,21 @@ int dppo_token_logprob(const dppo_head_shape* shape, const void* H, const void* 
     if (!H || !W || !ids || !logp) return fail(DPPO_ERR_INVALID_ARG, "a required array pointer is NULL");
     if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return fail(DPPO_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
     if (s.dtype == 1 && (!aligned16(H) || !aligned16(W))) return fail(DPPO_ERR_INVALID_ARG, "H and W must be 16-byte aligned");
+    if ((rc = check_min_workspace(s, false, ws_bytes)) != DPPO_OK) return rc;
+    int cus = DEFAULT_CUS;
+    if (s.dtype == 1 && (rc = mfma_setup(&cus)) != DPPO_OK) return rc;
     WsPlan p;
-    rc = plan_for(s, false, ws_bytes, p);
+    rc = plan_for(s, false, ws_bytes, cus, p);
     if (rc != DPPO_OK) return rc;
-    if (s.dtype == 1 && (rc = mfma_setup()) != DPPO_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     char* w = reinterpret_cast<char*>(ws);
+    if (status) launch_fill_zero(status, 4, st);
     for (int64_t n0 = 0; n0 < s.N; n0 += p.n_cp) {
         ChunkView cv;
         cv.n0 = n0;
         cv.n_c = (int32_t)((s.N - n0) < p.n_cp ? (s.N - n0) : p.n_cp);
         cv.n_cp = round_up32(cv.n_c, CHUNK_ALIGN);
-        if (int rc = chunk_forward(s, p, w, H, W, ids, loss_pos, cv, false, logp, lse, st)) return rc;
+        if (int rc = chunk_forward(s, p, w, H, W, ids, loss_pos, cv, false, logp, lse, status, st)) return rc;
     }
     return check_launch("dppo_token_logprob");
 }
@@ -405,8 +420,8 @@ int dppo_token_logprob(const dppo_head_shape* shape, const void* H, const void* 
 int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, int32_t S, const void* H,
                       const void* W, const int32_t* ids, const int32_t* loss_pos, const int32_t* loss_cu,
                       const float* seq_adv, const float* seq_coef, const float* logp_old, const float* logp_ref,
-                      float* loss, float* logp, float* seq_loss, float* stats, void* dH, float* dW, void* ws,
-                      size_t ws_bytes, void* stream) {
+                      float* loss, float* logp, float* seq_loss, float* stats, int32_t* status, void* dH, float* dW,
+                      void* ws, size_t ws_bytes, void* stream) {
     int rc = validate_shape(shape);
     if (rc != DPPO_OK) return rc;
     const dppo_head_shape& s = *shape;
@@ -426,10 +441,12 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
         return fail(DPPO_ERR_INVALID_ARG, "H, W, dH and dW must be 16-byte aligned");
     if (lp->recompute_logits != 0 && s.dtype != 1)
         return fail(DPPO_ERR_UNSUPPORTED, "recompute_logits is a bfloat16-path option");
+    if ((rc = check_min_workspace(s, true, ws_bytes)) != DPPO_OK) return rc;
+    int cus = DEFAULT_CUS;
+    if (s.dtype == 1 && (rc = mfma_setup(&cus)) != DPPO_OK) return rc;
     WsPlan p;
-    rc = plan_for(s, true, ws_bytes, p);
+    rc = plan_for(s, true, ws_bytes, cus, p);
     if (rc != DPPO_OK) return rc;
-    if (s.dtype == 1 && (rc = mfma_setup()) != DPPO_OK) return rc;
 
     hipStream_t st = (hipStream_t)stream;
     char* w = reinterpret_cast<char*>(ws);
@@ -439,6 +456,7 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
     float* clipf = reinterpret_cast<float*>(w + p.o_clip);
     float* seq_tmp = reinterpret_cast<float*>(w + p.o_seq);
 
+    if (status) launch_fill_zero(status, 4, st);
     launch_fill_zero(dH, (size_t)s.T * s.D * p.es, st);
     if (!lp->accumulate_dW && s.N == 0) launch_fill_zero(dW, (size_t)s.V * s.D * 4, st);
     if (s.N > 0) launch_transpose_w(s.dtype, W, s.V, s.D, p.Vp, w + p.o_wt, st);
@@ -452,7 +470,7 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
             cv.n0 = n0;
             cv.n_c = (int32_t)((s.N - n0) < p.n_cp ? (s.N - n0) : p.n_cp);
             cv.n_cp = round_up32(cv.n_c, CHUNK_ALIGN);
-            if (int rc = chunk_forward(s, p, w, H, W, ids, loss_pos, cv, false, logp_all, nullptr, st)) return rc;
+            if (int rc = chunk_forward(s, p, w, H, W, ids, loss_pos, cv, false, logp_all, nullptr, status, st)) return rc;
         }
         launch_seq_ratio(loss_cu, S, logp_all, logp_old, seq_ratio, st);
     }
@@ -464,7 +482,7 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
         cv.n_c = (int32_t)((s.N - n0) < p.n_cp ? (s.N - n0) : p.n_cp);
         cv.n_cp = round_up32(cv.n_c, CHUNK_ALIGN);
         const bool recompute = lp->recompute_logits != 0;
-        if (int rc = chunk_forward(s, p, w, H, W, ids, loss_pos, cv, s.dtype == 0 || !recompute, logp_all, nullptr, st)) return rc;
+        if (int rc = chunk_forward(s, p, w, H, W, ids, loss_pos, cv, s.dtype == 0 || !recompute, logp_all, nullptr, status, st)) return rc;
 
         TokenLossArgs ta;
         ta.loss_cu = loss_cu; ta.S = S; ta.seq_adv = seq_adv; ta.seq_coef = seq_coef;
@@ -504,7 +522,8 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
         // dH rows of the chunk: diag(row_scale) G[n_c, Vp] * WT[D, Vp]^T, scattered to the loss rows of dH
         StoreSpec oh;
         oh.out_bf16 = s.dtype == 1; oh.accumulate = 0; oh.ldc = s.D;
-        if (loss_pos) { oh.C = dH; oh.row_map = loss_pos; oh.row_base = n0; }
+        // the scatter goes through the chunk's clamped rows, so it stays inside dH whatever loss_pos holds
+        if (loss_pos) { oh.C = dH; oh.row_map = reinterpret_cast<const int32_t*>(w + p.o_rowc); oh.row_base = 0; }
         else { oh.C = reinterpret_cast<char*>(dH) + (size_t)n0 * s.D * p.es; oh.row_map = nullptr; oh.row_base = 0; }
         // dW[v, d] (+)= sum_n G[n, v] HcT[d, n]
         StoreSpec ow;
@@ -513,11 +532,11 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
         if (s.dtype == 1) {
             {
                 StageTimer tm(DPPO_STAGE_DH_GEMM, st);
-                launch_mfma_dh(G, p.Vp, w + p.o_wt, cv.n_c, s.D, row_scale, oh, reinterpret_cast<float*>(w + p.o_dwpart), st);
+                launch_mfma_dh(cus, G, p.Vp, w + p.o_wt, cv.n_c, s.D, row_scale, oh, reinterpret_cast<float*>(w + p.o_dwpart), st);
             }
             {
                 StageTimer tm(DPPO_STAGE_DW_GEMM, st);
-                launch_mfma_dw(G, p.Vp, w + p.o_hct, hct_pitch(1, cv.n_cp), cv.n_cp, s.V, s.D, ow,
+                launch_mfma_dw(cus, G, p.Vp, w + p.o_hct, hct_pitch(1, cv.n_cp), cv.n_cp, s.V, s.D, ow,
                                reinterpret_cast<float*>(w + p.o_dwpart), st);
             }
         } else {

@@ -42,11 +42,12 @@ struct ChunkView {
 };
 
 void launch_fill_zero(void* p, size_t bytes, hipStream_t st);
-// Hc[n_cp, D] = H[row(n0+n)] (zero rows beyond n_c); HcT[D, n_cp] its transpose (may be NULL);
-// y[n] = target id of loss token n0+n (clamped to [0,V)).
+// y[n] = target id of loss token n0+n and rowc[n] = its row of H, both clamped into range (a clamp
+// that changed something is OR-ed into *status, see DPPO_HEAD_BAD_*; status may be NULL);
+// Hc[n_cp, D] = H[rowc[n]] (zero rows beyond n_c); HcT[D, n_cp] its transpose (may be NULL).
 void launch_gather_rows(int dtype, const void* H, const int32_t* ids, const int32_t* loss_pos,
                         int64_t T, int32_t D, int32_t V, ChunkView cv, void* Hc, void* HcT,
-                        int32_t* y, hipStream_t st);
+                        int32_t* y, int32_t* rowc, int32_t* status, hipStream_t st);
 // WT[D, Vp] = transpose of W[V, D], columns v >= V zero.
 void launch_transpose_w(int dtype, const void* W, int32_t V, int32_t D, int32_t Vp, void* WT,
                         hipStream_t st);
@@ -132,7 +133,9 @@ void launch_gemm_plain_f32(const float* A, int64_t lda, const float* B, int64_t 
 
 // bf16 MFMA GEMMs (gemm_mfma.hip). K must be a multiple of 64; A and B rows may be read up
 // to the next multiple of the tile size, so operands are padded scratch buffers or clamped.
-int mfma_setup();   // one-time kernel attribute setup, returns dppo status
+// Kernel attribute setup for the current device (once per device) and its compute-unit count;
+// returns a dppo status.
+int mfma_setup(int* compute_units);
 // Vocabulary GEMM: rows = vocabulary entries (A = W[V,D]), columns = tokens (B = Hc[n_cp,D]).
 // Writes per-(row tile, token) partial (max, sum exp(z - max)) to part[tile*n_cp + n].
 int32_t mfma_logits_row_tiles(int32_t V);
@@ -153,14 +156,15 @@ int launch_mfma_logits_grad(const void* W, int32_t V, int32_t D, const void* Hc,
                             int32_t Vp, hipStream_t st);
 // dH rows of a chunk: C[n_c, D] = diag(row_scale) G[n_c, Vp] WT[D, Vp]^T with G in the blocked chunk
 // layout (pitch Vp); row_scale may be NULL (= 1). `partial`: as for launch_mfma_dw.
-void launch_mfma_dh(const void* G, int32_t Vp, const void* WT, int32_t n_c, int32_t D, const float* row_scale,
+void launch_mfma_dh(int cus, const void* G, int32_t Vp, const void* WT, int32_t n_c, int32_t D, const float* row_scale,
                     const StoreSpec& out, float* partial, hipStream_t st);
 // dW of a chunk: C[V, D] (+)= G^T HcT^T = sum_n G[n, v] HcT[d, n] (HcT row pitch ld_hct), G read k-major from the
 // same blocks.
 // `partial` is scratch of mfma_dw_partial_bytes() bytes (or NULL): with it, the tiles of a
-// sparsely filled last round are split along K over the idle compute units.
+// sparsely filled last round are split along K over the idle compute units (cus = compute units
+// of the device).
 size_t mfma_dw_partial_bytes();
-void launch_mfma_dw(const void* G, int32_t Vp, const void* HcT, int64_t ld_hct, int32_t n_cp, int32_t V, int32_t D,
+void launch_mfma_dw(int cus, const void* G, int32_t Vp, const void* HcT, int64_t ld_hct, int32_t n_cp, int32_t V, int32_t D,
                     const StoreSpec& out, float* partial, hipStream_t st);
 
 }  // namespace dppo

@@ -1,4 +1,6 @@
 // Instantiations and host launchers of the bf16 MFMA GEMM kernels (see gemm_mfma_kernel.h).
+#include <mutex>
+
 #include "gemm_mfma_kernel.h"
 
 namespace dppo {
@@ -83,22 +85,36 @@ hipError_t allow_lds() {
 
 }  // namespace
 
-int g_compute_units = 0;   // of the device the setup ran on
+// Per-device state: the dynamic-LDS attribute of every GEMM kernel and the number of compute
+// units, looked up once for each device a bfloat16 call runs on.
+namespace {
+constexpr int MAX_DEVICES = 64;
+struct DeviceState { bool done = false; int status = DPPO_OK; int cus = 0; };
+DeviceState g_dev[MAX_DEVICES];
+std::mutex g_dev_mu;
+}  // namespace
 
-int mfma_setup() {
-    static int status = [] {
-        int dev = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e == hipSuccess) e = hipDeviceGetAttribute(&g_compute_units, hipDeviceAttributeMultiprocessorCount, dev);
+int mfma_setup(int* compute_units) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(DPPO_ERR_DEVICE, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(DPPO_ERR_UNSUPPORTED, "device index %d", dev);
+    std::lock_guard<std::mutex> lk(g_dev_mu);
+    DeviceState& d = g_dev[dev];
+    if (!d.done) {
+        e = hipDeviceGetAttribute(&d.cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (e == hipSuccess) e = allow_lds<CfgGrad, EpiStoreDW, A_BLK_KM, WG_RANGES>();
         if (e == hipSuccess) e = allow_lds<CfgGrad, EpiStoreDH, A_BLK_ROWS, WG_RANGES>();
         if (e == hipSuccess) e = allow_lds<CfgBig, EpiLogits>();
         if (e == hipSuccess) e = allow_lds<CfgBig, EpiLogitsExp>();
         if (e == hipSuccess) e = allow_lds<CfgBig, EpiLogitsGrad>();
-        if (e != hipSuccess) return fail(DPPO_ERR_DEVICE, "hipFuncSetAttribute(dynamic LDS): %s", hipGetErrorString(e));
-        return (int)DPPO_OK;
-    }();
-    return status;
+        d.status = e == hipSuccess ? (int)DPPO_OK
+                                   : fail(DPPO_ERR_DEVICE, "device %d setup (dynamic LDS): %s", dev, hipGetErrorString(e));
+        d.done = e == hipSuccess;    // a failed setup is tried again by the next call
+        if (e != hipSuccess) return d.status;
+    }
+    if (compute_units) *compute_units = d.cus;
+    return d.status;
 }
 
 int32_t mfma_logits_row_tiles(int32_t V) { return (int32_t)ceil_div(V, CfgBig::BM); }
@@ -139,8 +155,7 @@ size_t mfma_dw_partial_bytes() { return (size_t)256 * CfgBig::BM * CfgBig::BN * 
 // most 8, at least 16 slices each), each part writes its partial tile to scratch, and a small
 // kernel adds the parts up in order (the same sums in a different association; deterministic).
 // Returns the number of parts (1 = no split) and the number of tail tiles.
-static int tail_split(int tiles, int k_slices, const float* partial, int& tail) {
-    const int cus = g_compute_units;
+static int tail_split(int cus, int tiles, int k_slices, const float* partial, int& tail) {
     tail = cus > 0 ? tiles % cus : 0;
     int parts = 1;
     if (partial && tail > 0 && 2 * tail <= cus) {
@@ -152,13 +167,13 @@ static int tail_split(int tiles, int k_slices, const float* partial, int& tail) 
     return parts < 2 ? 1 : parts;
 }
 
-void launch_mfma_dh(const void* G, int32_t Vp, const void* WT, int32_t n_c, int32_t D, const float* row_scale,
+void launch_mfma_dh(int cus, const void* G, int32_t Vp, const void* WT, int32_t n_c, int32_t D, const float* row_scale,
                     const StoreSpec& out, float* partial, hipStream_t st) {
     EpiStoreDH e{nullptr, reinterpret_cast<uint16_t*>(out.C), out.ldc, 0, out.row_map, out.row_base, row_scale, nullptr};
     const int tiles_m = (int)ceil_div(n_c, CfgGrad::BM), tiles_n = (int)ceil_div(D, CfgGrad::BN);
     const int tiles = tiles_m * tiles_n;
     int tail;
-    const int parts = tail_split(tiles, Vp / CfgGrad::BK, partial, tail);
+    const int parts = tail_split(cus, tiles, Vp / CfgGrad::BK, partial, tail);
     if (parts == 1) {
         launch<CfgGrad, A_BLK_ROWS, WG_RANGES>(G, Vp, WT, Vp, n_c, D, Vp, e, st);
         return;
@@ -172,13 +187,13 @@ void launch_mfma_dh(const void* G, int32_t Vp, const void* WT, int32_t n_c, int3
         out.row_map, out.row_base, row_scale);
 }
 
-void launch_mfma_dw(const void* G, int32_t Vp, const void* HcT, int64_t ld_hct, int32_t n_cp, int32_t V, int32_t D,
+void launch_mfma_dw(int cus, const void* G, int32_t Vp, const void* HcT, int64_t ld_hct, int32_t n_cp, int32_t V, int32_t D,
                     const StoreSpec& out, float* partial, hipStream_t st) {
     EpiStoreDW e{reinterpret_cast<float*>(out.C), nullptr, out.ldc, out.accumulate, nullptr, 0, nullptr, nullptr};
     const int tiles_m = (int)ceil_div(V, CfgGrad::BM), tiles_n = (int)ceil_div(D, CfgGrad::BN);
     const int tiles = tiles_m * tiles_n;
     int tail;
-    const int parts = tail_split(tiles, n_cp / CfgGrad::BK, partial, tail);
+    const int parts = tail_split(cus, tiles, n_cp / CfgGrad::BK, partial, tail);
     if (parts == 1) {
         launch<CfgGrad, A_BLK_KM, WG_RANGES>(G, Vp, HcT, ld_hct, V, D, n_cp, e, st);
         return;

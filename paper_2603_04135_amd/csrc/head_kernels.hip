@@ -56,18 +56,30 @@ __global__ __launch_bounds__(256) void gather_transpose_kernel(
     }
 }
 
+// Target id and (clamped) row of H of every loss token of the chunk. An id outside [0, V) or a
+// position outside [0, T) is clamped into the range and reported in *status, so that every later
+// gather and scatter of the call stays in bounds.
 __global__ void targets_kernel(const int32_t* __restrict__ ids, const int32_t* __restrict__ loss_pos, int64_t T,
-                               int32_t V, int64_t n0, int32_t n_c, int32_t n_cp, int32_t* __restrict__ y) {
+                               int32_t V, int64_t n0, int32_t n_c, int32_t n_cp, int32_t* __restrict__ y,
+                               int32_t* __restrict__ rowc, int32_t* status) {
     const int n = blockIdx.x * blockDim.x + threadIdx.x;
     if (n >= n_cp) return;
-    int32_t t = 0;
+    int32_t t = 0, row = 0;
+    int flags = 0;
     if (n < n_c) {
-        int64_t pos = loss_pos ? (int64_t)loss_pos[n0 + n] + 1 : n0 + n;
+        int64_t r = loss_pos ? (int64_t)loss_pos[n0 + n] : n0 + n;
+        int64_t pos = loss_pos ? r + 1 : r;
+        if (r < 0 || pos >= T) flags |= DPPO_HEAD_BAD_POSITION;
+        r = r < 0 ? 0 : (r >= T ? T - 1 : r);
         pos = pos < 0 ? 0 : (pos >= T ? T - 1 : pos);
         t = ids[pos];
+        if (t < 0 || t >= V) flags |= DPPO_HEAD_BAD_TARGET;
         t = t < 0 ? 0 : (t >= V ? V - 1 : t);
+        row = (int32_t)r;
     }
     y[n] = t;
+    rowc[n] = row;
+    if (flags != 0 && status != nullptr) atomicOr(status, flags);
 }
 
 // ------------------------------------------------------------------------------------
@@ -479,7 +491,7 @@ __global__ __launch_bounds__(256) void seq_ratio_kernel(const int32_t* __restric
             if (threadIdx.x < st) r0[threadIdx.x] += r0[threadIdx.x + st];
             __syncthreads();
         }
-        if (threadIdx.x == 0) seq_ratio[s] = expf(r0[0] / (float)(e - b));
+        if (threadIdx.x == 0) seq_ratio[s] = e > b ? expf(r0[0] / (float)(e - b)) : 1.0f;
         __syncthreads();
     }
 }
@@ -514,7 +526,8 @@ __global__ __launch_bounds__(256) void seq_reduce_kernel(SeqReduceArgs a) {
             __syncthreads();
         }
         if (threadIdx.x == 0) {
-            const float mean = a.aggregation == DPPO_AGG_TOKEN_SUM ? r0[0] : r0[0] / (float)(e - b);
+            // an empty segment contributes nothing (its sums are 0)
+            const float mean = (a.aggregation == DPPO_AGG_TOKEN_SUM || e <= b) ? r0[0] : r0[0] / (float)(e - b);
             a.seq_mean[s] = mean;
             a.seq_kl[s] = r1[0];
             a.seq_clip[s] = r2[0];
@@ -569,23 +582,24 @@ void launch_fill_zero(void* p, size_t bytes, hipStream_t st) {
 }
 
 void launch_gather_rows(int dtype, const void* H, const int32_t* ids, const int32_t* loss_pos, int64_t T,
-                        int32_t D, int32_t V, ChunkView cv, void* Hc, void* HcT, int32_t* y, hipStream_t st) {
+                        int32_t D, int32_t V, ChunkView cv, void* Hc, void* HcT, int32_t* y, int32_t* rowc,
+                        int32_t* status, hipStream_t st) {
+    targets_kernel<<<(unsigned)ceil_div(cv.n_cp, 256), 256, 0, st>>>(ids, loss_pos, T, V, cv.n0, cv.n_c, cv.n_cp, y,
+                                                                     rowc, status);
     dim3 grid((unsigned)ceil_div(D, 64), (unsigned)(cv.n_cp / 64));
     if (dtype == 1 && HcT == nullptr && D % 8 == 0) {
         const int64_t n_vec = (int64_t)cv.n_cp * (D / 8);
         gather_rows_bf16_kernel<<<(unsigned)ceil_div(n_vec, 256), 256, 0, st>>>(
-            reinterpret_cast<const uint4*>(H), D / 8, loss_pos, cv.n0, cv.n0, T, cv.n_c, cv.n_cp,
-            reinterpret_cast<uint4*>(Hc));
+            reinterpret_cast<const uint4*>(H), D / 8, rowc, 0, 0, T, cv.n_c, cv.n_cp, reinterpret_cast<uint4*>(Hc));
     } else if (dtype == 1) {
         gather_transpose_kernel<uint16_t><<<grid, 256, 0, st>>>(
-            reinterpret_cast<const uint16_t*>(H), D, loss_pos, cv.n0, cv.n0, T, cv.n_c, D, cv.n_cp, D,
+            reinterpret_cast<const uint16_t*>(H), D, rowc, 0, 0, T, cv.n_c, D, cv.n_cp, D,
             reinterpret_cast<uint16_t*>(Hc), D, reinterpret_cast<uint16_t*>(HcT), cv.n_cp);
     } else {
         gather_transpose_kernel<float><<<grid, 256, 0, st>>>(
-            reinterpret_cast<const float*>(H), D, loss_pos, cv.n0, cv.n0, T, cv.n_c, D, cv.n_cp, D,
+            reinterpret_cast<const float*>(H), D, rowc, 0, 0, T, cv.n_c, D, cv.n_cp, D,
             reinterpret_cast<float*>(Hc), D, reinterpret_cast<float*>(HcT), cv.n_cp);
     }
-    targets_kernel<<<(unsigned)ceil_div(cv.n_cp, 256), 256, 0, st>>>(ids, loss_pos, T, V, cv.n0, cv.n_c, cv.n_cp, y);
 }
 
 void launch_transpose_w(int dtype, const void* W, int32_t V, int32_t D, int32_t Vp, void* WT, hipStream_t st) {

@@ -165,7 +165,11 @@ __global__ __launch_bounds__(WAVE) void pack_kernel(
     }
     if (lane == 0) {
         meta[0] = rows; meta[1] = (int32_t)T; meta[2] = (int32_t)N; meta[3] = 0;
-        meta[4] = S; meta[5] = capacity; meta[6] = 0; meta[7] = 0;
+        meta[4] = S; meta[5] = capacity;
+        // fill density T / (rows * capacity) as the two halves of a double (low word first)
+        const double dens = rows > 0 ? (double)T / ((double)rows * (double)capacity) : 0.0;
+        const uint64_t bits = (uint64_t)__double_as_longlong(dens);
+        meta[6] = (int32_t)(uint32_t)(bits & 0xffffffffull); meta[7] = (int32_t)(uint32_t)(bits >> 32);
     }
 }
 

@@ -136,28 +136,39 @@ def test_whole_batch_sampled_against_oracle(lib, name):
     assert stats[2] == N and 0.0 < stats[1] < 1.0 and stats[0] > 0.0
 
     # (e) sampled dW rows, dW[v] = sum_n c_n (1[y_n = v] - exp(z_nv - lse_n)) H_n, in float64 by plain
-    # tensor arithmetic over ALL loss tokens; c_n by the oracle's token terms from the log-probs
-    # that (a) sampled, lse_n = z_{n,y_n} - logp_n. Rows from the first tile, the middle, the
-    # frequent targets, and the last tile rows (the tiles of the dW GEMM's last round, which are
-    # computed in K-split parts).
+    # tensor arithmetic over ALL loss tokens. Nothing here comes from the library: lse_n is the
+    # log-sum-exp of H_n W^T from a float32 library matmul of the widened operands, z_{n,y_n} a float64
+    # dot product, c_n the oracle's token terms of logp_n = z_{n,y_n} - lse_n. Rows from the first tile,
+    # the middle, the frequent targets, and the last tile rows (the tiles of the dW GEMM's last
+    # round, which are computed in K-split parts).
     y_all = ids_np[loss_pos + 1]
     s_all = np.searchsorted(loss_cu, np.arange(N), side="right") - 1
-    _, g_all, _, _ = O.token_terms(logp_gpu.astype(np.float64), old_np.astype(np.float64), ref_np.astype(np.float64),
+    y_t = torch.as_tensor(y_all, device=DEV).long()
+    lpos_t = torch.as_tensor(loss_pos, device=DEV).long()
+    W32 = W.float()
+    lse_t = torch.empty(N, dtype=torch.float64, device=DEV)
+    zy_t = torch.empty(N, dtype=torch.float64, device=DEV)
+    for i in range(0, N, 1 << 13):
+        j = min(N, i + (1 << 13))
+        Hn = H[lpos_t[i:j]]
+        lse_t[i:j] = torch.logsumexp(Hn.float() @ W32.T, dim=1).double()
+        zy_t[i:j] = (Hn.double() * W[y_t[i:j]].double()).sum(dim=1)
+    del W32
+    logp_ind = (zy_t - lse_t).cpu().numpy()
+    assert np.abs(logp_ind[pick] - logp_o).max() <= 1e-4          # the independent log-probs against the oracle's
+    _, g_all, _, _ = O.token_terms(logp_ind, old_np.astype(np.float64), ref_np.astype(np.float64),
                                    adv_s[s_all].astype(np.float64), wl.clip_eps, wl.clip_eps, wl.kl_beta)
     c_all = coef_s[s_all].astype(np.float64) / np.diff(loss_cu)[s_all] * g_all
     vs = np.unique(np.concatenate([[0, 255, 256, wl.V // 2, wl.V - 1, wl.V - 300, max(wl.V - 1000, 0)],
                                    np.bincount(y_all, minlength=wl.V).argsort()[-2:]]))
     Wv = W[torch.as_tensor(vs, device=DEV).long()].double()
     ref_rows = torch.zeros((len(vs), wl.D), dtype=torch.float64, device=DEV)
-    lp_t, c_t = torch.as_tensor(logp_gpu, device=DEV).double(), torch.as_tensor(c_all, device=DEV)
-    y_t, vs_t = torch.as_tensor(y_all, device=DEV).long(), torch.as_tensor(vs, device=DEV).long()
-    lpos_t = torch.as_tensor(loss_pos, device=DEV).long()
+    c_t = torch.as_tensor(c_all, device=DEV)
+    vs_t = torch.as_tensor(vs, device=DEV).long()
     for i in range(0, N, 1 << 15):
         j = min(N, i + (1 << 15))
         Hn = H[lpos_t[i:j]].double()
-        zy = (Hn * W[y_t[i:j]].double()).sum(dim=1)
-        lse_n = zy - lp_t[i:j]
-        Pn = torch.exp(Hn @ Wv.T - lse_n[:, None])
+        Pn = torch.exp(Hn @ Wv.T - lse_t[i:j, None])
         Gn = c_t[i:j, None] * ((y_t[i:j, None] == vs_t[None, :]).double() - Pn)
         ref_rows += Gn.T @ Hn
     got_rows = dW[vs_t].double()

@@ -49,6 +49,8 @@ def test_host_side_validation_launches_nothing(lib):
     assert lib.dppo_select(ctypes.byref(sp), *([one] * 14), None) == 2
     sp = SelectParams(4, 4, 0.5, 0.5, 1e-6, 1, 0.5, 0, 1)
     assert lib.dppo_select(ctypes.byref(sp), None, *([one] * 13), None) == 1
+    sp = SelectParams(4, 4, 0.5, 0.5, 0.0, 1, 0.5, 0, 1)        # adv_eps = 0: a constant group would divide 0 by 0
+    assert lib.dppo_select(ctypes.byref(sp), *([one] * 14), None) == 1
     pp = PackParams(0, 16, 4, 0)
     assert lib.dppo_pack(ctypes.byref(pp), *([one] * 8), 10, one, None) == 2
     pp = PackParams(4, 16, 0, 0)
@@ -58,16 +60,16 @@ def test_host_side_validation_launches_nothing(lib):
     pp = PackParams(4, 1, 4, 0)                           # capacity below a 1+1 token item
     assert lib.dppo_pack(ctypes.byref(pp), *([one] * 8), 10, one, None) == 3
     hs = HeadShape(100, 50, 72, 1000, 1)                  # bf16 needs D % 64 == 0
-    assert lib.dppo_token_logprob(ctypes.byref(hs), *([one] * 7), 1 << 20, None) == 5
+    assert lib.dppo_token_logprob(ctypes.byref(hs), *([one] * 8), 1 << 20, None) == 5
     assert lib.dppo_workspace_bytes(ctypes.byref(hs), 1) == 0
     hs = HeadShape(100, 200, 64, 1000, 1)                 # N > T
-    assert lib.dppo_token_logprob(ctypes.byref(hs), *([one] * 7), 1 << 20, None) == 2
+    assert lib.dppo_token_logprob(ctypes.byref(hs), *([one] * 8), 1 << 20, None) == 2
     hs = HeadShape(100, 50, 64, 1000, 1)
     lp = LossParams(0.2, 0.2, 0.04, 0, 0)
-    assert lib.dppo_loss_fwd_bwd(ctypes.byref(hs), ctypes.byref(lp), 3, *([one] * 15), one, 1024, None) == 4
-    assert lib.dppo_token_logprob(ctypes.byref(hs), *([one] * 6), None, 1 << 20, None) == 4
+    assert lib.dppo_loss_fwd_bwd(ctypes.byref(hs), ctypes.byref(lp), 3, *([one] * 16), one, 1024, None) == 4
+    assert lib.dppo_token_logprob(ctypes.byref(hs), *([one] * 7), None, 1 << 20, None) == 4
     lp = LossParams(0.2, 0.2, 0.04, 0, 0, 2, 0)          # unknown ratio level
-    assert lib.dppo_loss_fwd_bwd(ctypes.byref(hs), ctypes.byref(lp), 3, *([one] * 15), one, 1 << 30, None) == 1
+    assert lib.dppo_loss_fwd_bwd(ctypes.byref(hs), ctypes.byref(lp), 3, *([one] * 16), one, 1 << 30, None) == 1
     assert lib.dppo_token_norm_coef(0, 4, one, one, one, None) == 2
     assert lib.dppo_variance_terms(4, 0, one, one, one, one, one, None) == 2
     assert lib.dppo_variance_terms(4, 4, one, None, one, one, one, None) == 1
