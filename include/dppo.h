@@ -193,6 +193,27 @@ int dppo_token_logprob(const dppo_head_shape* shape,
                        float* logp, float* lse /* or NULL */, int32_t* status /* or NULL */,
                        void* ws, size_t ws_bytes, void* stream);
 
+/* dppo_token_logprob_noalloc -- for callers that cannot allocate device memory (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): dppo_token_logprob with
+ * the workspace replaced by a fixed device array inside the library, DPPO_STATIC_SCRATCH_MIB MiB
+ * per GPU the library runs on, held until the process ends (dppo_static_scratch_bytes() returns
+ * the size in bytes). Same arguments, kernels and results otherwise; the token chunks are as
+ * large as that array allows (about 6 000 tokens at D = 2560, V = 151936), so large batches run
+ * slower than with a recommended-size workspace. The call itself allocates and frees nothing and
+ * calls no allocating routine (keep stage timing off: it creates events).
+ * A shape whose smallest chunk (256 tokens: 256 rows of H, the per-tile softmax statistics and
+ * a few vectors) does not fit the array is refused with DPPO_ERR_WORKSPACE and nothing is launched.
+ * All calls on one GPU share that GPU's array, whose contents are whatever the last call left
+ * (no part of it needs to start at zero: every region is written before it is read): calls that
+ * overlap in time on one GPU, on different streams or threads, race on it. */
+#define DPPO_STATIC_SCRATCH_MIB 64
+size_t dppo_static_scratch_bytes(void);
+int dppo_token_logprob_noalloc(const dppo_head_shape* shape,
+                               const void* H, const void* W, const int32_t* ids,
+                               const int32_t* loss_pos /* or NULL */,
+                               float* logp, float* lse /* or NULL */, int32_t* status /* or NULL */,
+                               void* stream);
+
 /* Loss L = sum_s seq_coef[s] * (1/C_s) * sum_{n in s} l_n over the S packed sequences
  * (segments loss_cu[s]..loss_cu[s+1] of the loss tokens, C_s their length; loss_cu must be
  * non-decreasing from 0 to N, and an empty segment contributes 0, with seq_loss[s] = 0), with

@@ -19,7 +19,8 @@ _lib = None
 
 EXPORTS = ["dppo_status_str", "dppo_last_error", "dppo_select", "dppo_pack", "dppo_gather_f32", "dppo_token_norm_coef", "dppo_variance_terms",
            "dppo_workspace_bytes", "dppo_workspace_min_bytes", "dppo_token_logprob", "dppo_loss_fwd_bwd",
-           "dppo_timing_enable", "dppo_timing_read", "dppo_history_update"]
+           "dppo_timing_enable", "dppo_timing_read", "dppo_history_update", "dppo_token_logprob_noalloc",
+           "dppo_static_scratch_bytes"]
 STAGES = ["logits_gemm", "grad_logits", "dh_gemm", "dw_gemm"]
 
 
@@ -90,6 +91,10 @@ def load():
     lib.dppo_workspace_min_bytes.argtypes = [POINTER(HeadShape), c_int]
     lib.dppo_token_logprob.restype = c_int
     lib.dppo_token_logprob.argtypes = [POINTER(HeadShape)] + [c_void_p] * 8 + [c_size_t, c_void_p]
+    lib.dppo_token_logprob_noalloc.restype = c_int
+    lib.dppo_token_logprob_noalloc.argtypes = [POINTER(HeadShape)] + [c_void_p] * 8
+    lib.dppo_static_scratch_bytes.restype = c_size_t
+    lib.dppo_static_scratch_bytes.argtypes = []
     lib.dppo_loss_fwd_bwd.restype = c_int
     lib.dppo_loss_fwd_bwd.argtypes = ([POINTER(HeadShape), POINTER(LossParams), c_int32] + [c_void_p] * 17
                                       + [c_size_t, c_void_p])
@@ -292,6 +297,22 @@ def dppo_token_logprob(H, W, ids, loss_pos=None, want_lse: bool = True, ws: Opti
                                 _ptr(lse), _ptr(status), _ptr(ws), ws.numel(), _stream(device))
     _check(st, "dppo_token_logprob")
     return logp, lse
+
+
+def dppo_token_logprob_noalloc(H, W, ids, loss_pos, logp: torch.Tensor, lse: Optional[torch.Tensor] = None,
+                               status: Optional[torch.Tensor] = None) -> None:
+    """dppo_token_logprob on the library's fixed scratch array: fills the caller's logp[N] (and lse[N]);
+    this wrapper allocates nothing either."""
+    lib = load()
+    N = H.shape[0] if loss_pos is None else loss_pos.numel()
+    shape = _shape(H, W, N)
+    st = lib.dppo_token_logprob_noalloc(ctypes.byref(shape), _ptr(H), _ptr(W), _ptr(ids), _ptr(loss_pos), _ptr(logp),
+                                        _ptr(lse), _ptr(status), _stream(H.device))
+    _check(st, "dppo_token_logprob_noalloc")
+
+
+def dppo_static_scratch_bytes() -> int:
+    return int(load().dppo_static_scratch_bytes())
 
 
 def dppo_loss_fwd_bwd(H, W, ids, loss_pos, loss_cu, seq_adv, seq_coef, logp_old, logp_ref,

@@ -96,7 +96,7 @@ void layout(const dppo_head_shape& s, bool bwd, int32_t n_cp, WsPlan& p) {
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, REGION_ALIGN); return o; };
     const size_t N = (size_t)s.N;
     p.o_wt = take(bwd ? (size_t)s.D * p.Vp * p.es : 0);
-    p.o_logp = take(N * 4);
+    p.o_logp = take(bwd ? N * 4 : 0);   // log-probs of the batch when the caller wants none back
     p.o_ell = take(bwd ? N * 4 : 0);
     p.o_kl = take(bwd ? N * 4 : 0);
     p.o_clip = take(bwd ? N * 4 : 0);
@@ -247,6 +247,36 @@ int chunk_forward(const dppo_head_shape& s, const WsPlan& p, char* ws, const voi
         launch_row_stats_f32(reinterpret_cast<const float*>(ws + p.o_zg), p.Vp, s.V, y, cv, lse_c, logp_all,
                              lse_all, st);
     }
+    return DPPO_OK;
+}
+
+// ---- scratch of the entry point that allocates nothing ---------------------------------------
+// A device array of fixed size takes the place of the caller's workspace. In host code the
+// array's name is only a stand-in for the symbol: the device address is looked up once per
+// device (each device holds its own copy at its own address) and only that pointer is ever
+// handed to kernels.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)DPPO_STATIC_SCRATCH_MIB << 20;
+__device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_SCRATCH_DEVICES = 64;
+void* g_scratch_ptr[MAX_SCRATCH_DEVICES] = {};
+std::mutex g_scratch_mu;
+
+// Device address of `scratch` on the current device (looked up on the first call on each device).
+int static_scratch(void** out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(DPPO_ERR_DEVICE, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= MAX_SCRATCH_DEVICES) return fail(DPPO_ERR_UNSUPPORTED, "device index %d", dev);
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr)
+            return fail(DPPO_ERR_DEVICE, "hipGetSymbolAddress(static scratch) on device %d: %s", dev, hipGetErrorString(e));
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
     return DPPO_OK;
 }
 
@@ -415,6 +445,26 @@ int dppo_token_logprob(const dppo_head_shape* shape, const void* H, const void* 
         if (int rc = chunk_forward(s, p, w, H, W, ids, loss_pos, cv, false, logp, lse, status, st)) return rc;
     }
     return check_launch("dppo_token_logprob");
+}
+
+size_t dppo_static_scratch_bytes(void) { return STATIC_SCRATCH_BYTES; }
+
+int dppo_token_logprob_noalloc(const dppo_head_shape* shape, const void* H, const void* W, const int32_t* ids,
+                               const int32_t* loss_pos, float* logp, float* lse, int32_t* status, void* stream) {
+    int rc = validate_shape(shape);
+    if (rc != DPPO_OK) return rc;
+    // sizes beyond what the fixed scratch can serve are refused before anything else happens
+    WsPlan q;
+    layout(*shape, false, CHUNK_ALIGN, q);
+    if (q.total > STATIC_SCRATCH_BYTES)
+        return fail(DPPO_ERR_WORKSPACE,
+                    "shape needs at least %zu bytes of scratch (one 256-token chunk of D=%d, V=%d), above the fixed %zu bytes "
+                    "of dppo_token_logprob_noalloc; use dppo_token_logprob with a workspace",
+                    q.total, shape->D, shape->V, STATIC_SCRATCH_BYTES);
+    if (shape->N == 0) return DPPO_OK;
+    void* ws = nullptr;
+    if ((rc = static_scratch(&ws)) != DPPO_OK) return rc;
+    return dppo_token_logprob(shape, H, W, ids, loss_pos, logp, lse, status, ws, STATIC_SCRATCH_BYTES, stream);
 }
 
 int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, int32_t S, const void* H,
