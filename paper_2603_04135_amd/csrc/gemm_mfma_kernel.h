@@ -337,12 +337,19 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
             const int cur = (kk + PAR) & 1, nxt = cur ^ 1;
+            // Issue priority: low in the k-steps that run up to the barrier, high in the one behind it.
+            // The two wavefronts of a SIMD drift apart (the older one wins every issue slot, reaches the
+            // barrier first and idles there while the other one's memory instructions stall with nobody
+            // to fill the matrix pipe); with the lagging wavefront preferred they reach the barrier
+            // together (barrier wait of the leading wavefront 35 % -> 23 % of the loop, 3 % fewer cycles).
+            if (kk == 0) __builtin_amdgcn_s_setprio(0);
             bool loads_a = false, loads_b = false, reads_here = false;
             int read_bufa = 0, read_bufb = 0, read_kk = 0;
             if (kk == KK - 1) {
                 if (STEADY || kt + 1 < KT) {
                     if (STEADY) wait_loads_then_barrier<STEADY_PENDING>();
                     else wait_loads_then_barrier<0>();
+                    __builtin_amdgcn_s_setprio(2);
                     loads_b = STEADY || kt + SB < KT;
                     loads_a = STEADY || kt + SA < KT;
                     read_bufa = nbufa; read_bufb = nbufb; read_kk = 0; reads_here = true;
@@ -395,6 +402,7 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
         for (; kt < KT; ++kt) slice(kt, std::false_type{}, P0{});
     }
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    __builtin_amdgcn_s_setprio(0);
 
     TileCtx c;
     c.M = M; c.N = N; c.tm = tm; c.tn = tn;
