@@ -297,10 +297,21 @@ enum {
     DPPO_STAGE_GRAD_LOGITS = 1, /* softmax-gradient pass over the stored chunk (float32), row scales (bfloat16) */
     DPPO_STAGE_DH_GEMM = 2,     /* dH = G W                                               */
     DPPO_STAGE_DW_GEMM = 3,     /* dW += G^T H                                            */
-    DPPO_N_STAGES = 4
+    DPPO_STAGE_ELEMENTWISE = 4, /* every other kernel of the two LM-head calls: row gather, transposes,
+                                   target logits, combination of the per-tile statistics, token loss
+                                   terms, zero fill of dH, the segmented reduction (HBM-bound)  */
+    DPPO_N_STAGES = 5
 };
 int dppo_timing_enable(int on);
 int dppo_timing_read(double* ms /* [DPPO_N_STAGES] */, int64_t* launches /* [DPPO_N_STAGES] */, int reset);
+
+/* Benchmark aid: enqueues a loop of `iters` x 32 bf16 MFMA instructions (the GEMMs' own, 16x16x32)
+ * per wavefront, 8 wavefronts on every compute unit, operands in registers only (random_operands 0:
+ * all ones, 1: pseudo-random values in [-1, 1]: the chip's power limit makes the sustained rate depend
+ * on the data). *flop (host) receives the floating-point operations enqueued; the caller times the
+ * stream and divides: that rate is the ceiling the GEMM stages can be compared with. out (device):
+ * at least one float per compute unit of the device (out_floats says how many it holds). */
+int dppo_mfma_rate_probe(int random_operands, int iters, float* out, int32_t out_floats, double* flop, void* stream);
 
 #ifdef __cplusplus
 }

@@ -20,8 +20,8 @@ _lib = None
 EXPORTS = ["dppo_status_str", "dppo_last_error", "dppo_select", "dppo_pack", "dppo_gather_f32", "dppo_token_norm_coef", "dppo_variance_terms",
            "dppo_workspace_bytes", "dppo_workspace_min_bytes", "dppo_token_logprob", "dppo_loss_fwd_bwd",
            "dppo_timing_enable", "dppo_timing_read", "dppo_history_update", "dppo_token_logprob_noalloc",
-           "dppo_static_scratch_bytes"]
-STAGES = ["logits_gemm", "grad_logits", "dh_gemm", "dw_gemm"]
+           "dppo_static_scratch_bytes", "dppo_mfma_rate_probe"]
+STAGES = ["logits_gemm", "grad_logits", "dh_gemm", "dw_gemm", "elementwise"]
 
 
 class DppoError(RuntimeError):
@@ -95,6 +95,8 @@ def load():
     lib.dppo_token_logprob_noalloc.argtypes = [POINTER(HeadShape)] + [c_void_p] * 8
     lib.dppo_static_scratch_bytes.restype = c_size_t
     lib.dppo_static_scratch_bytes.argtypes = []
+    lib.dppo_mfma_rate_probe.restype = c_int
+    lib.dppo_mfma_rate_probe.argtypes = [c_int, c_int, c_void_p, c_int32, POINTER(ctypes.c_double), c_void_p]
     lib.dppo_loss_fwd_bwd.restype = c_int
     lib.dppo_loss_fwd_bwd.argtypes = ([POINTER(HeadShape), POINTER(LossParams), c_int32] + [c_void_p] * 17
                                       + [c_size_t, c_void_p])
@@ -353,6 +355,14 @@ def dppo_loss_fwd_bwd(H, W, ids, loss_pos, loss_cu, seq_adv, seq_coef, logp_old,
     res["dH"] = dH
     res["dW"] = dW
     return res
+
+
+def dppo_mfma_rate_probe(random_operands: bool, iters: int, out: torch.Tensor) -> float:
+    """Enqueues the register-only MFMA loop on the current stream; returns the flop enqueued (the caller times it)."""
+    flop = ctypes.c_double(0.0)
+    _check(load().dppo_mfma_rate_probe(1 if random_operands else 0, iters, _ptr(out), out.numel(), ctypes.byref(flop),
+                                       _stream(out.device)), "dppo_mfma_rate_probe")
+    return float(flop.value)
 
 
 def dppo_timing_enable(on: bool) -> None:

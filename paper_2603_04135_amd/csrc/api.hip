@@ -212,8 +212,11 @@ int chunk_forward(const dppo_head_shape& s, const WsPlan& p, char* ws, const voi
     int32_t* y = reinterpret_cast<int32_t*>(ws + p.o_y);
     float* zy = reinterpret_cast<float*>(ws + p.o_zy);
     float* lse_c = reinterpret_cast<float*>(ws + p.o_lse);
-    launch_gather_rows(s.dtype, H, ids, loss_pos, s.T, s.D, s.V, cv, Hc, keep_z && s.dtype == 0 ? ws + p.o_hct : nullptr,
-                       y, reinterpret_cast<int32_t*>(ws + p.o_rowc), status, st);
+    {
+        StageTimer tm(DPPO_STAGE_ELEMENTWISE, st);
+        launch_gather_rows(s.dtype, H, ids, loss_pos, s.T, s.D, s.V, cv, Hc, keep_z && s.dtype == 0 ? ws + p.o_hct : nullptr,
+                           y, reinterpret_cast<int32_t*>(ws + p.o_rowc), status, st);
+    }
     if (s.dtype == 1 && keep_z) {
         float2* part = reinterpret_cast<float2*>(ws + p.o_part);
         float* bref = reinterpret_cast<float*>(ws + p.o_bref);
@@ -223,12 +226,16 @@ int chunk_forward(const dppo_head_shape& s, const WsPlan& p, char* ws, const voi
         float* redo_sum = reinterpret_cast<float*>(ws + p.o_redo_sum);
         // reference of the stored exponentials = the target logit: lse - reference = -logp of a
         // token that was sampled from (nearly) this policy, a few units in any sane batch
-        launch_target_logit(1, Hc, W, y, cv.n_cp, s.D, zy, bref, redo_count, st);
+        {
+            StageTimer tm(DPPO_STAGE_ELEMENTWISE, st);
+            launch_target_logit(1, Hc, W, y, cv.n_cp, s.D, zy, bref, redo_count, st);
+        }
         {
             StageTimer tm(DPPO_STAGE_LOGITS_GEMM, st);
             const int rc = launch_mfma_logits_exp(W, s.V, s.D, Hc, cv.n_cp, part, bref, ws + p.o_zg, p.Vp, p.Vp, st);
             if (rc != DPPO_OK) return rc;
         }
+        StageTimer tm(DPPO_STAGE_ELEMENTWISE, st);
         launch_combine_exp(part, p.n_tiles, zy, bref, cv, lse_c, logp_all, mx, redo_count, redo_list, redo_sum, st);
         launch_exp_redo_rows(redo_count, redo_list, redo_sum, Hc, W, s.V, p.Vp, s.D, zy, mx, cv, ws + p.o_zg, p.Vp,
                              bref, lse_c, logp_all, st);
@@ -238,6 +245,7 @@ int chunk_forward(const dppo_head_shape& s, const WsPlan& p, char* ws, const voi
             StageTimer tm(DPPO_STAGE_LOGITS_GEMM, st);
             launch_mfma_logits(W, s.V, s.D, Hc, cv.n_cp, part, st);
         }
+        StageTimer tm(DPPO_STAGE_ELEMENTWISE, st);
         launch_target_logit(1, Hc, W, y, cv.n_cp, s.D, zy, nullptr, nullptr, st);
         launch_combine_logprob(part, p.n_tiles, zy, cv, lse_c, logp_all, lse_all, st);
     } else {
@@ -404,6 +412,16 @@ int dppo_timing_read(double* ms, int64_t* launches, int reset) {
     return DPPO_OK;
 }
 
+int dppo_mfma_rate_probe(int random_operands, int iters, float* out, int32_t out_floats, double* flop, void* stream) {
+    if (iters <= 0 || !out || !flop) return fail(DPPO_ERR_INVALID_ARG, "iters must be positive, out and flop not NULL");
+    int cus = 0;
+    const int rc = mfma_setup(&cus);
+    if (rc != DPPO_OK) return rc;
+    if (out_floats < cus) return fail(DPPO_ERR_SHAPE, "out holds %d floats, the device has %d compute units", out_floats, cus);
+    *flop = launch_mfma_rate_probe(cus, iters, random_operands != 0, out, (hipStream_t)stream);
+    return check_launch("dppo_mfma_rate_probe");
+}
+
 size_t dppo_workspace_bytes(const dppo_head_shape* shape, int want_backward) {
     if (validate_shape(shape) != DPPO_OK) return 0;
     WsPlan p;
@@ -507,9 +525,12 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
     float* seq_tmp = reinterpret_cast<float*>(w + p.o_seq);
 
     if (status) launch_fill_zero(status, 4, st);
-    launch_fill_zero(dH, (size_t)s.T * s.D * p.es, st);
-    if (!lp->accumulate_dW && s.N == 0) launch_fill_zero(dW, (size_t)s.V * s.D * 4, st);
-    if (s.N > 0) launch_transpose_w(s.dtype, W, s.V, s.D, p.Vp, w + p.o_wt, st);
+    {
+        StageTimer tm(DPPO_STAGE_ELEMENTWISE, st);
+        launch_fill_zero(dH, (size_t)s.T * s.D * p.es, st);
+        if (!lp->accumulate_dW && s.N == 0) launch_fill_zero(dW, (size_t)s.V * s.D * 4, st);
+        if (s.N > 0) launch_transpose_w(s.dtype, W, s.V, s.D, p.Vp, w + p.o_wt, st);
+    }
 
     float* seq_ratio = reinterpret_cast<float*>(w + p.o_sratio);
     if (lp->ratio_level == DPPO_RATIO_SEQUENCE && s.N > 0) {
@@ -541,7 +562,10 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
         ta.ratio_level = lp->ratio_level; ta.aggregation = lp->aggregation; ta.seq_ratio = seq_ratio;
         ta.c_chunk = reinterpret_cast<float*>(w + p.o_c);
         ta.ell = ell; ta.kl = kl; ta.clipped = clipf;
-        launch_token_loss(ta, cv, st);
+        {
+            StageTimer tm(DPPO_STAGE_ELEMENTWISE, st);
+            launch_token_loss(ta, cv, st);
+        }
 
         const int32_t* y = reinterpret_cast<const int32_t*>(w + p.o_y);
         const float* lse_c = reinterpret_cast<const float*>(w + p.o_lse);
@@ -566,8 +590,10 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
                                  lse_c, ta.c_chunk, cv, G, p.Vp, scale, st);
             row_scale = scale;
         }
-        if (s.dtype == 1)
+        if (s.dtype == 1) {
+            StageTimer tm(DPPO_STAGE_ELEMENTWISE, st);
             launch_scale_transpose_bf16(w + p.o_hc, row_scale, cv.n_cp, s.D, w + p.o_hct, hct_pitch(1, cv.n_cp), st);
+        }
 
         // dH rows of the chunk: diag(row_scale) G[n_c, Vp] * WT[D, Vp]^T, scattered to the loss rows of dH
         StoreSpec oh;
@@ -604,7 +630,10 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
     ra.ell = ell; ra.kl = kl; ra.clipped = clipf;
     ra.seq_mean = seq_tmp; ra.seq_kl = seq_tmp + s.N; ra.seq_clip = seq_tmp + 2 * s.N;
     ra.seq_loss_out = seq_loss; ra.loss_out = loss; ra.stats_out = stats;
-    launch_seq_reduce(ra, st);
+    {
+        StageTimer tm(DPPO_STAGE_ELEMENTWISE, st);
+        launch_seq_reduce(ra, st);
+    }
     return check_launch("dppo_loss_fwd_bwd");
 }
 

@@ -167,4 +167,7 @@ size_t mfma_dw_partial_bytes();
 void launch_mfma_dw(int cus, const void* G, int32_t Vp, const void* HcT, int64_t ld_hct, int32_t n_cp, int32_t V, int32_t D,
                     const StoreSpec& out, float* partial, hipStream_t st);
 
+// Register-only MFMA loop on `cus` workgroups (benchmark aid); returns the flop it enqueues. out: cus floats.
+double launch_mfma_rate_probe(int cus, int iters, int random_values, float* out, hipStream_t st);
+
 }  // namespace dppo

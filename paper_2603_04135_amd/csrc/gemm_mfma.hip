@@ -207,4 +207,45 @@ void launch_mfma_dw(int cus, const void* G, int32_t Vp, const void* HcT, int64_t
         nullptr, nullptr, 0, nullptr);
 }
 
+// Register-only loop of the GEMMs' MFMA instruction (8 wavefronts per compute unit, 32 independent
+// accumulator blocks each, operands never leave the registers): the rate the matrix pipes sustain
+// when nothing has to be loaded, which is the ceiling the GEMMs are priced against. With random operand
+// values the chip's power limit lowers the clock, so the ceiling depends on the data.
+namespace {
+__device__ __forceinline__ mfma::bf16x8 probe_operand(unsigned seed, int random_values) {
+    mfma::bf16x8 v;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        unsigned h = (seed * 8u + (unsigned)i) * 2654435761u;
+        h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+        const float f = random_values ? (float)((int)(h % 2001u) - 1000) * 0.001f : 1.0f;
+        v[i] = (__bf16)f;
+    }
+    return v;
+}
+__global__ __launch_bounds__(512) void mfma_rate_kernel(float* out, int iters, int random_values) {
+    mfma::bf16x8 a[8], b[4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a[i] = probe_operand(threadIdx.x * 7u + (unsigned)i + blockIdx.x * 1000u, random_values);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) b[i] = probe_operand(threadIdx.x * 13u + (unsigned)i + 77u, random_values);
+    mfma::f32x4 acc[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) acc[i] = mfma::f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int q = 0; q < 32; ++q) acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[q / 4], b[q % 4], acc[q], 0, 0, 0);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) s += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+    if (threadIdx.x == 0) out[blockIdx.x] = s;      // keeps the loop alive; one float per workgroup
+}
+}  // namespace
+
+double launch_mfma_rate_probe(int cus, int iters, int random_values, float* out, hipStream_t st) {
+    mfma_rate_kernel<<<cus, 512, 0, st>>>(out, iters, random_values);
+    return (double)cus * 8.0 * (double)iters * 32.0 * 16384.0;   // 8 wavefronts x 32 MFMAs x 2 x 16 x 16 x 32 flop
+}
+
 }  // namespace dppo
