@@ -149,12 +149,18 @@ __host__ __device__ __forceinline__ size_t blk_offset(int64_t r, int64_t c, int6
 // Tile walk: tiles are numbered in bands of GROUP_M tile rows, column by column inside a band.
 template <int GROUP_M>
 __host__ __device__ __forceinline__ void tile_coords(int tile, int tiles_m, int tiles_n, int& tm, int& tn) {
+    // (one runtime division: this runs at the head of every workgroup, before its first load)
     const int band_sz = GROUP_M * tiles_n;
-    const int band = tile / band_sz, in_band = tile % band_sz;
+    const int band = tile / band_sz, in_band = tile - band * band_sz;
     const int first_m = band * GROUP_M;
-    const int gm = (tiles_m - first_m) < GROUP_M ? (tiles_m - first_m) : GROUP_M;
-    tm = first_m + in_band % gm;
-    tn = in_band / gm;
+    if (tiles_m - first_m >= GROUP_M) {          // a full band: GROUP_M is a compile-time constant
+        tm = first_m + in_band % GROUP_M;
+        tn = in_band / GROUP_M;
+    } else {
+        const int gm = tiles_m - first_m;
+        tm = first_m + in_band % gm;
+        tn = in_band / gm;
+    }
 }
 
 // A launch covers gridDim.x work items: item i is part i % k_parts of tile tile0 + i / k_parts,
@@ -195,10 +201,14 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
         }
     }
     int tm, tn;
-    tile_coords<Cfg::GROUP_M>(tile0 + logical / k_parts, tiles_m, tiles_n, tm, tn);
-    const int k_part = logical % k_parts;
-    const int kt_lo = (int)((int64_t)k_part * (K / Cfg::BK) / k_parts);
-    const int kt_hi = (int)((int64_t)(k_part + 1) * (K / Cfg::BK) / k_parts);
+    int kt_lo = 0, kt_hi = K / Cfg::BK, item_tile = logical;
+    if (k_parts != 1) {                          // whole tiles (the common case) skip these divisions
+        item_tile = logical / k_parts;
+        const int k_part = logical - item_tile * k_parts;
+        kt_lo = (int)((int64_t)k_part * (K / Cfg::BK) / k_parts);
+        kt_hi = (int)((int64_t)(k_part + 1) * (K / Cfg::BK) / k_parts);
+    }
+    tile_coords<Cfg::GROUP_M>(tile0 + item_tile, tiles_m, tiles_n, tm, tn);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps LDS targets in SGPRs
     const int wave_m = wave % Cfg::WGM, wave_n = wave / Cfg::WGM;
