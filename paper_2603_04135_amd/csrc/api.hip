@@ -64,6 +64,14 @@ struct StageTimer {
 
 constexpr int32_t CHUNK_ALIGN = 256;      // token-chunk granularity (= GEMM tile edge)
 constexpr int32_t CHUNK_MAX = 32768;      // largest token chunk
+// The chunk's gathered hidden states [n_cp, D] are the operand that every tile row of the vocabulary GEMM
+// (and, transposed, of the dW GEMM) reads again; they must stay resident in the 256 MB Infinity Cache next
+// to the W panels streaming through it (a 268 MB chunk, 32768 tokens of D = 4096, runs 7 % slower per token).
+constexpr size_t CHUNK_CACHE_BYTES = (size_t)192 << 20;
+int32_t chunk_max_for(int32_t D, size_t es) {
+    const int64_t fit = (int64_t)(CHUNK_CACHE_BYTES / ((size_t)D * es)) / CHUNK_ALIGN * CHUNK_ALIGN;
+    return (int32_t)(fit < CHUNK_ALIGN ? CHUNK_ALIGN : (fit > CHUNK_MAX ? CHUNK_MAX : fit));
+}
 constexpr size_t REGION_ALIGN = 256;
 
 struct WsPlan {
@@ -132,11 +140,11 @@ void layout(const dppo_head_shape& s, bool bwd, int32_t n_cp, WsPlan& p) {
 // small kernels, ramps).
 constexpr int DEFAULT_CUS = 256;          // MI355X; used where no device is at hand (size queries)
 constexpr double CHUNK_OVERHEAD_ROUNDS = 0.35;
-int32_t target_chunk(int64_t N, int32_t D, int cus) {
+int32_t target_chunk(int64_t N, int32_t D, size_t es, int cus) {
     if (N <= 0) return CHUNK_ALIGN;
     const int64_t CHIP_CUS = cus > 0 ? cus : DEFAULT_CUS;
     const int64_t tiles_n = ceil_div(D, 256);
-    const int64_t c0 = ceil_div(N, CHUNK_MAX);
+    const int64_t c0 = ceil_div(N, chunk_max_for(D, es));
     double best = 0.0;
     int64_t best_c = c0;
     for (int64_t c = c0; c <= c0 + 6; ++c) {
@@ -175,7 +183,7 @@ int check_min_workspace(const dppo_head_shape& s, bool bwd, size_t ws_bytes) {
 
 // Picks the largest chunk that fits `ws_bytes` (at most the balanced target chunk).
 int plan_for(const dppo_head_shape& s, bool bwd, size_t ws_bytes, int cus, WsPlan& p) {
-    const int32_t target = target_chunk(s.N, s.D, cus);
+    const int32_t target = target_chunk(s.N, s.D, s.dtype == 1 ? 2 : 4, cus);
     layout(s, bwd, target, p);
     if (p.total > ws_bytes) {
         WsPlan q;
@@ -425,7 +433,7 @@ int dppo_mfma_rate_probe(int random_operands, int iters, float* out, int32_t out
 size_t dppo_workspace_bytes(const dppo_head_shape* shape, int want_backward) {
     if (validate_shape(shape) != DPPO_OK) return 0;
     WsPlan p;
-    layout(*shape, want_backward != 0, target_chunk(shape->N, shape->D, DEFAULT_CUS), p);
+    layout(*shape, want_backward != 0, target_chunk(shape->N, shape->D, shape->dtype == 1 ? 2 : 4, DEFAULT_CUS), p);
     return p.total;
 }
 
