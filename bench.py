@@ -15,6 +15,8 @@ What the line holds besides the contract fields:
                                  elementwise kernels timed on their own, with algorithmic bytes and GB/s;
   roofline                       the slowest GEMM stage against the bf16 MFMA peak, and against the rate a
                                  register-only loop of the same MFMA sustains in this run (achievable);
+  tile_phases                    shader cycles the GEMM workgroups spend before their first slice is in LDS, in the
+                                 main loop and in the epilogue, against the cycles their MFMAs alone need;
   cpu_baseline                   the NumPy oracle on a bounded sample, on all host cores and on one.
 """
 from __future__ import annotations
@@ -37,6 +39,9 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E peak
 # gives). Keyed by (workload, kernel, recompute); an entry is deleted when that kernel changes, until
 # the counters are taken again.
 MEASURED_TRAFFIC_BYTES = {
+    ("qwen3_4b", "logits_gemm", False): 2.0 * 19049053 * 1024 + 9734622 * 1024,
+    ("qwen3_4b", "dh_gemm", False): 2.0 * 21310769 * 1024 + 161247 * 1024,
+    ("qwen3_4b", "dw_gemm", False): 2.0 * 22063136 * 1024 + 1560944 * 1024,   # both dispatches
 }
 
 
@@ -301,6 +306,28 @@ def main() -> int:
         roofline["achievable"] = rates["random_operands"]
         roofline["frac_of_achievable"] = achieved / rates["random_operands"]
         roofline["register_only_mfma_tflops"] = rates
+    # ---- where the GEMM workgroups spend their cycles: one more step with the tile-phase counters on ----
+    tile_phases = None
+    if dtype_code == 1:
+        counters = torch.zeros(12, dtype=torch.int64, device=dev)
+        P.dppo_timing_tile_phases(counters)
+        step()
+        torch.cuda.synchronize()
+        P.dppo_timing_tile_phases(None)
+        c = counters.cpu().tolist()
+        Vp = -(-wl.V // 256) * 256
+        n_cp = -(-int(round(N / n_chunks)) // 256) * 256
+        slices = {"logits_gemm": wl.D / 64.0, "dh_gemm": Vp / 64.0, "dw_gemm": n_cp / 64.0}
+        tile_phases = {}
+        for i, name in enumerate(("logits_gemm", "dh_gemm", "dw_gemm")):
+            pro, loop, epi, n = c[4 * i:4 * i + 4]
+            if n == 0:
+                continue
+            ideal = slices[name] * 2 * 64 * 16      # 2 wavefronts per SIMD x 64 MFMAs per slice x 16 cycles
+            tot = (pro + loop + epi) / n
+            tile_phases[name] = {"workgroups": n, "cycles_prologue": pro / n, "cycles_main_loop": loop / n,
+                                 "cycles_epilogue": epi / n, "mfma_cycles_of_a_tile": ideal,
+                                 "main_loop_mfma_share": ideal / (loop / n), "tile_mfma_share": ideal / tot}
     stage_ms = {k: v[0] / args.steps for k, v in stages.items()}
     mfu = 6.0 * wl.D * wl.V * N / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
 
@@ -352,6 +379,7 @@ def main() -> int:
         "stages": other,
         "loss": loss,
         "roofline": roofline,
+        "tile_phases": tile_phases,
         "vendor_blas": vendor,
         "cpu_baseline": cpu,
     }

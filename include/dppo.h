@@ -305,6 +305,14 @@ enum {
 int dppo_timing_enable(int on);
 int dppo_timing_read(double* ms /* [DPPO_N_STAGES] */, int64_t* launches /* [DPPO_N_STAGES] */, int reset);
 
+/* Benchmark aid: where the workgroups of the three big GEMMs spend their time. counters: device array of
+ * 12 uint64 the caller has zeroed, {vocabulary GEMM, dH GEMM, dW GEMM} x {shader cycles from the start of a
+ * workgroup until its first operand slice is in LDS, cycles in the main loop, cycles in the epilogue, number of
+ * workgroups}; while set, every whole-tile launch of the bfloat16 LM-head calls adds to it (4 atomic
+ * adds per workgroup; the launches that split K are left out). NULL switches it off. Process-wide state,
+ * like the stage timing; the array must outlive the launches that write it. */
+int dppo_timing_tile_phases(uint64_t* counters);
+
 /* Benchmark aid: enqueues a loop of `iters` x 32 bf16 MFMA instructions (the GEMMs' own, 16x16x32)
  * per wavefront, 8 wavefronts on every compute unit, operands in registers only (random_operands 0:
  * all ones, 1: pseudo-random values in [-1, 1]: the chip's power limit makes the sustained rate depend

@@ -20,7 +20,7 @@ _lib = None
 EXPORTS = ["dppo_status_str", "dppo_last_error", "dppo_select", "dppo_pack", "dppo_gather_f32", "dppo_token_norm_coef", "dppo_variance_terms",
            "dppo_workspace_bytes", "dppo_workspace_min_bytes", "dppo_token_logprob", "dppo_loss_fwd_bwd",
            "dppo_timing_enable", "dppo_timing_read", "dppo_history_update", "dppo_token_logprob_noalloc",
-           "dppo_static_scratch_bytes", "dppo_mfma_rate_probe"]
+           "dppo_static_scratch_bytes", "dppo_mfma_rate_probe", "dppo_timing_tile_phases"]
 STAGES = ["logits_gemm", "grad_logits", "dh_gemm", "dw_gemm", "elementwise"]
 
 
@@ -95,6 +95,8 @@ def load():
     lib.dppo_token_logprob_noalloc.argtypes = [POINTER(HeadShape)] + [c_void_p] * 8
     lib.dppo_static_scratch_bytes.restype = c_size_t
     lib.dppo_static_scratch_bytes.argtypes = []
+    lib.dppo_timing_tile_phases.restype = c_int
+    lib.dppo_timing_tile_phases.argtypes = [c_void_p]
     lib.dppo_mfma_rate_probe.restype = c_int
     lib.dppo_mfma_rate_probe.argtypes = [c_int, c_int, c_void_p, c_int32, POINTER(ctypes.c_double), c_void_p]
     lib.dppo_loss_fwd_bwd.restype = c_int
@@ -363,6 +365,13 @@ def dppo_mfma_rate_probe(random_operands: bool, iters: int, out: torch.Tensor) -
     _check(load().dppo_mfma_rate_probe(1 if random_operands else 0, iters, _ptr(out), out.numel(), ctypes.byref(flop),
                                        _stream(out.device)), "dppo_mfma_rate_probe")
     return float(flop.value)
+
+
+def dppo_timing_tile_phases(counters: Optional[torch.Tensor]) -> None:
+    """counters: zeroed int64[12] device tensor (3 GEMM stages x {prologue, loop, epilogue cycles, workgroups}) or None."""
+    if counters is not None and (counters.dtype != torch.int64 or counters.numel() < 12):
+        raise ValueError("counters must be an int64 device tensor of at least 12 elements")
+    _check(load().dppo_timing_tile_phases(_ptr(counters)), "dppo_timing_tile_phases")
 
 
 def dppo_timing_enable(on: bool) -> None:

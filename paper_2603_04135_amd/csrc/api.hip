@@ -420,6 +420,11 @@ int dppo_timing_read(double* ms, int64_t* launches, int reset) {
     return DPPO_OK;
 }
 
+int dppo_timing_tile_phases(uint64_t* counters) {
+    mfma_set_phase_counters(reinterpret_cast<unsigned long long*>(counters));
+    return DPPO_OK;
+}
+
 int dppo_mfma_rate_probe(int random_operands, int iters, float* out, int32_t out_floats, double* flop, void* stream) {
     if (iters <= 0 || !out || !flop) return fail(DPPO_ERR_INVALID_ARG, "iters must be positive, out and flop not NULL");
     int cus = 0;

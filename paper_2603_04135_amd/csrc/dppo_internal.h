@@ -167,6 +167,9 @@ size_t mfma_dw_partial_bytes();
 void launch_mfma_dw(int cus, const void* G, int32_t Vp, const void* HcT, int64_t ld_hct, int32_t n_cp, int32_t V, int32_t D,
                     const StoreSpec& out, float* partial, hipStream_t st);
 
+// Benchmark aid: device array of 12 counters (3 GEMM stages x {prologue, main loop, epilogue cycles, tiles})
+// that the whole-tile launches of the vocabulary, dH and dW GEMMs add to; NULL switches it off.
+void mfma_set_phase_counters(unsigned long long* counters);
 // Register-only MFMA loop on `cus` workgroups (benchmark aid); returns the flop it enqueues. out: cus floats.
 double launch_mfma_rate_probe(int cus, int iters, int random_values, float* out, hipStream_t st);
 

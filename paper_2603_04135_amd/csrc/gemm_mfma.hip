@@ -1,4 +1,5 @@
 // Instantiations and host launchers of the bf16 MFMA GEMM kernels (see gemm_mfma_kernel.h).
+#include <atomic>
 #include <mutex>
 
 #include "gemm_mfma_kernel.h"
@@ -29,15 +30,21 @@ constexpr int lds_request() {
 
 // Launches the tiles [tile0, tile0 + n_tiles) of the tile walk, each cut into k_parts work items
 // along K; n_tiles < 0: all tiles.
+// Tile-phase counters of the benchmark aid (NULL = off): 4 counters per GEMM stage, see gemm_nt_kernel.
+std::atomic<unsigned long long*> g_phase_counters{nullptr};
+enum { PHASE_LOGITS = 0, PHASE_DH = 1, PHASE_DW = 2 };
+
 template <class Cfg, int AM = A_ROWS, int MAP = WG_ROUNDS, class Epi>
 void launch(const void* A, int64_t lda, const void* B, int64_t ldb, int M, int N, int K, const Epi& epi,
-            hipStream_t st, int tile0 = 0, int n_tiles = -1, int k_parts = 1) {
+            hipStream_t st, int tile0 = 0, int n_tiles = -1, int k_parts = 1, int phase_stage = -1) {
     const int tiles_m = (int)ceil_div(M, Cfg::BM), tiles_n = (int)ceil_div(N, Cfg::BN);
     if (n_tiles < 0) n_tiles = tiles_m * tiles_n - tile0;
     if (n_tiles <= 0) return;
+    unsigned long long* phase = phase_stage >= 0 && k_parts == 1 ? g_phase_counters.load() : nullptr;
+    if (phase) phase += 4 * phase_stage;
     gemm_nt_kernel<Cfg, Epi, AM, MAP><<<dim3(n_tiles * k_parts), dim3(Cfg::NT), lds_request<Cfg, Epi>(), st>>>(
         reinterpret_cast<const uint16_t*>(A), lda, reinterpret_cast<const uint16_t*>(B), ldb, M, N, K, tiles_m,
-        tiles_n, tile0, k_parts, epi);
+        tiles_n, tile0, k_parts, epi, phase);
 }
 
 // Sums the k_parts partial tiles of each of the n_tiles tiles from tile0 on, in part order, into
@@ -117,13 +124,15 @@ int mfma_setup(int* compute_units) {
     return d.status;
 }
 
+void mfma_set_phase_counters(unsigned long long* counters) { g_phase_counters.store(counters); }
+
 int32_t mfma_logits_row_tiles(int32_t V) { return (int32_t)ceil_div(V, CfgBig::BM); }
 int32_t mfma_vocab_tile() { return CfgBig::BM; }
 
 void launch_mfma_logits(const void* W, int32_t V, int32_t D, const void* Hc, int32_t n_cp, float2* part,
                         hipStream_t st) {
     EpiLogits e{part, n_cp};
-    launch<CfgBig>(W, D, Hc, D, V, n_cp, D, e, st);
+    launch<CfgBig>(W, D, Hc, D, V, n_cp, D, e, st, 0, -1, 1, PHASE_LOGITS);
 }
 
 int launch_mfma_logits_exp(const void* W, int32_t V, int32_t D, const void* Hc, int32_t n_cp, float2* part,
@@ -133,7 +142,7 @@ int launch_mfma_logits_exp(const void* W, int32_t V, int32_t D, const void* Hc, 
         return fail(DPPO_ERR_UNSUPPORTED, "chunk buffer not padded to whole vocabulary tiles (Vp %d, pitch %lld)", Vp,
                     (long long)lde);
     EpiLogitsExp e{part, n_cp, bref, reinterpret_cast<uint16_t*>(E), lde};
-    launch<CfgBig>(W, D, Hc, D, V, n_cp, D, e, st);
+    launch<CfgBig>(W, D, Hc, D, V, n_cp, D, e, st, 0, -1, 1, PHASE_LOGITS);
     return DPPO_OK;
 }
 
@@ -175,10 +184,10 @@ void launch_mfma_dh(int cus, const void* G, int32_t Vp, const void* WT, int32_t 
     int tail;
     const int parts = tail_split(cus, tiles, Vp / CfgGrad::BK, partial, tail);
     if (parts == 1) {
-        launch<CfgGrad, A_BLK_ROWS, WG_RANGES>(G, Vp, WT, Vp, n_c, D, Vp, e, st);
+        launch<CfgGrad, A_BLK_ROWS, WG_RANGES>(G, Vp, WT, Vp, n_c, D, Vp, e, st, 0, -1, 1, PHASE_DH);
         return;
     }
-    launch<CfgGrad, A_BLK_ROWS, WG_RANGES>(G, Vp, WT, Vp, n_c, D, Vp, e, st, 0, tiles - tail, 1);
+    launch<CfgGrad, A_BLK_ROWS, WG_RANGES>(G, Vp, WT, Vp, n_c, D, Vp, e, st, 0, tiles - tail, 1, PHASE_DH);
     EpiStoreDH ep = e;
     ep.partial = partial;
     launch<CfgGrad, A_BLK_ROWS, WG_RANGES>(G, Vp, WT, Vp, n_c, D, Vp, ep, st, tiles - tail, tail, parts);
@@ -195,10 +204,10 @@ void launch_mfma_dw(int cus, const void* G, int32_t Vp, const void* HcT, int64_t
     int tail;
     const int parts = tail_split(cus, tiles, n_cp / CfgGrad::BK, partial, tail);
     if (parts == 1) {
-        launch<CfgGrad, A_BLK_KM, WG_RANGES>(G, Vp, HcT, ld_hct, V, D, n_cp, e, st);
+        launch<CfgGrad, A_BLK_KM, WG_RANGES>(G, Vp, HcT, ld_hct, V, D, n_cp, e, st, 0, -1, 1, PHASE_DW);
         return;
     }
-    launch<CfgGrad, A_BLK_KM, WG_RANGES>(G, Vp, HcT, ld_hct, V, D, n_cp, e, st, 0, tiles - tail, 1);
+    launch<CfgGrad, A_BLK_KM, WG_RANGES>(G, Vp, HcT, ld_hct, V, D, n_cp, e, st, 0, tiles - tail, 1, PHASE_DW);
     EpiStoreDW ep = e;
     ep.partial = partial;
     launch<CfgGrad, A_BLK_KM, WG_RANGES>(G, Vp, HcT, ld_hct, V, D, n_cp, ep, st, tiles - tail, tail, parts);

@@ -171,8 +171,12 @@ template <class Cfg, class Epi, int AM = A_ROWS, int MAP = WG_ROUNDS>
 __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __restrict__ A, int64_t lda,
                                                           const uint16_t* __restrict__ B, int64_t ldb, int M,
                                                           int N, int K, int tiles_m, int tiles_n, int tile0,
-                                                          int k_parts, Epi epi) {
+                                                          int k_parts, Epi epi, unsigned long long* phase) {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
+    // phase (benchmark aid, normally NULL): 4 counters that every workgroup adds to: shader cycles from
+    // its start to the first slice in LDS, in the main loop, in the epilogue, and 1.
+    unsigned long long pt0 = 0, pt1 = 0, pt2 = 0;
+    if (phase) pt0 = clock64();
     constexpr bool A_KM = AM == A_BLK_KM;
     constexpr int MI = Cfg::MI, NI = Cfg::NI, KK = Cfg::KK, LPS = Cfg::LPS;
     constexpr int ROWB = Cfg::ROWB, CPR = Cfg::CPR;
@@ -326,6 +330,7 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
     // loads issued behind B of slice 0: A of slices 1 .. SA-1 and B of slices 1 .. SB-1
     if (KT >= SA) wait_loads_then_barrier<(SA - 1) * A_LD + (SB - 1) * B_LD>();
     else wait_loads_then_barrier<0>();
+    if (phase) pt1 = clock64();
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) read_a(a_slot(mi, 0), smem, 0, mi);
 #pragma unroll
@@ -413,6 +418,7 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
     }
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
     __builtin_amdgcn_s_setprio(0);
+    if (phase) pt2 = clock64();
 
     TileCtx c;
     c.M = M; c.N = N; c.tm = tm; c.tn = tn;
@@ -420,6 +426,13 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
     c.m0 = bm0 + wave_m * Cfg::WTM; c.n0 = bn0 + wave_n * Cfg::WTN;
     c.wave_m = wave_m; c.wave_n = wave_n; c.lane = lane; c.tid = tid; c.item = logical; c.smem = smem;
     epi.template run<Cfg>(acc, c);
+    if (phase && tid == 0) {
+        const unsigned long long pt3 = clock64();
+        atomicAdd(phase + 0, pt1 - pt0);
+        atomicAdd(phase + 1, pt2 - pt1);
+        atomicAdd(phase + 2, pt3 - pt2);
+        atomicAdd(phase + 3, 1ull);
+    }
 }
 
 // ---------------------------------------------------------------------------------------
