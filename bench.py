@@ -340,12 +340,16 @@ def main() -> int:
         Hc = torch.randn((n_c, wl.D), device=dev).to(bf)
         Wm = (torch.randn((wl.V, wl.D), device=dev) * 0.02).to(bf)
         E = torch.exp(torch.randn((n_c, wl.V), device=dev, dtype=bf).float() - 12.0).to(bf)
-        shapes = {"logits (W Hc^T)": (Wm, Hc.t()), "dH (E W)": (E, Wm), "dW (E^T Hc)": (E.t(), Hc)}
+        WT, HcT, ET = Wm.t().contiguous(), Hc.t().contiguous(), E.t().contiguous()
+        shapes = {"logits (W Hc^T)": (Wm, Hc.t()), "dH (E W)": (E, Wm), "dW (E^T Hc)": (E.t(), Hc),
+                  # the same two with every operand as a K-contiguous copy (the layout BLAS kernels like best;
+                  # the library makes the W^T and Hc^T copies itself but never a transposed copy of the chunk)
+                  "dH, W^T copy given": (E, WT.t()), "dW, E^T and Hc^T copies given": (ET, HcT.t())}
         vendor = {}
         for k, (a_, b_) in shapes.items():
             ms = timed(lambda: torch.mm(a_, b_), 5)
             vendor[k] = {"ms": ms, "TFLOP/s": 2.0 * n_c * wl.V * wl.D / (ms * 1e-3) / 1e12}
-        del Hc, Wm, E
+        del Hc, Wm, E, WT, HcT, ET
 
     if args.calibrate_copy:
         src = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
