@@ -118,6 +118,9 @@ def main() -> int:
     ap.add_argument("--cpu-sample", type=int, default=2048, help="loss tokens the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--cpu-sample-1t", type=int, default=256, help="loss tokens of the single-thread oracle leg")
     ap.add_argument("--recompute", action="store_true", help="recompute the logits in the backward")
+    ap.add_argument("--ratio-level", choices=("token", "sequence"), default="token",
+                    help="token = Eq. 1 (the benchmark); sequence = the sequence-level ratio variant, with the longest "
+                         "sequence promised to the library so that its forward runs one chunk ahead (context only)")
     ap.add_argument("--vendor-gemm", action="store_true",
                     help="also time the vendor BLAS (torch.mm) on the three GEMM shapes of one chunk, same value distributions")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -166,7 +169,9 @@ def main() -> int:
     ids = torch.as_tensor(ids_np, device=dev)
     dtype_code = 0 if wl.dtype == "f32" else 1
     es = 4 if dtype_code == 0 else 2
-    ws = P.alloc_workspace(P.dppo_workspace_bytes(T, N, wl.D, wl.V, dtype_code, True), dev)
+    seq_level = args.ratio_level == "sequence"
+    max_seq = int(rb.comp_len.max()) if seq_level else 0
+    ws = P.alloc_workspace(P.dppo_workspace_bytes(T, N, wl.D, wl.V, dtype_code, 2 if seq_level else 1), dev)
     base, _ = P.dppo_token_logprob(H, W, ids, pk["loss_pos"], want_lse=False, ws=ws)
     base_np = base.cpu().numpy()
     logp_old = torch.as_tensor(WL.perturb_logp(base_np, wl.logp_noise, seed, 0), device=dev)
@@ -189,7 +194,8 @@ def main() -> int:
             a.record()
         out = P.dppo_loss_fwd_bwd(H, W, ids, pk["loss_pos"], pk["loss_cu"], seq_adv, seq_coef, logp_old, logp_ref,
                                   wl.clip_eps, wl.clip_eps, wl.kl_beta, dW=dW, dH=dH, ws=ws, out=outbuf,
-                                  recompute_logits=args.recompute, status=status)
+                                  recompute_logits=args.recompute, status=status, ratio_level=args.ratio_level,
+                                  max_seq_tokens=max_seq)
         if record:
             b.record()
             loss_events.append((a, b))
@@ -373,7 +379,7 @@ def main() -> int:
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": args.workload, "Q": wl.Q, "G": wl.G, "D": wl.D, "V": wl.V,
                    "loss_tokens_N": N, "packed_tokens_T": T, "sequences_S": S,
-                   "recompute_logits": bool(args.recompute)},
+                   "recompute_logits": bool(args.recompute), "ratio_level": args.ratio_level},
         "mfu_6dv_frac_of_bf16_peak": mfu,
         "packed_tokens_T_per_s": T / (ms_per_step * 1e-3),
         "loss_fwd_bwd_ms": {"median": med_call, "min": min(call_ms), "max": max(call_ms),

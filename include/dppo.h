@@ -169,10 +169,13 @@ int dppo_gather_f32(int64_t n, const int32_t* idx, const float* src, float* dst,
  *   DPPO_HEAD_BAD_TARGET    a target id outside [0,V): the id is clamped into the range;
  *   DPPO_HEAD_BAD_POSITION  a loss_pos entry p with p < 0 or p + 1 >= T: the row and its target
  *                           position are clamped into [0,T).
+ *   DPPO_HEAD_SEQ_TOO_LONG  (dppo_loss_fwd_bwd with the sequence-level ratio) a sequence has more
+ *                           loss tokens than dppo_loss_params.max_seq_tokens promised and its
+ *                           ratio was not complete when its first tokens' gradients were formed.
  * Every kernel still runs to the end and every output is defined; what the outputs mean for the
  * offending tokens is up to the caller. Entries of loss_pos must be distinct (not checked).
  */
-enum { DPPO_HEAD_BAD_TARGET = 1, DPPO_HEAD_BAD_POSITION = 2 };
+enum { DPPO_HEAD_BAD_TARGET = 1, DPPO_HEAD_BAD_POSITION = 2, DPPO_HEAD_SEQ_TOO_LONG = 4 };
 
 typedef struct {
     int64_t T, N;
@@ -181,7 +184,9 @@ typedef struct {
 } dppo_head_shape;
 
 /* Recommended workspace size in bytes (0 if the shape is invalid). Any size of at least
- * dppo_workspace_min_bytes works: a smaller workspace means smaller token chunks. */
+ * dppo_workspace_min_bytes works: a smaller workspace means smaller token chunks.
+ * want_backward (both calls): 0 = dppo_token_logprob, 1 = dppo_loss_fwd_bwd, 2 = dppo_loss_fwd_bwd
+ * with the sequence-level ratio and max_seq_tokens given (two sets of per-chunk regions). */
 size_t dppo_workspace_bytes(const dppo_head_shape* shape, int want_backward);
 size_t dppo_workspace_min_bytes(const dppo_head_shape* shape, int want_backward);
 
@@ -236,8 +241,14 @@ int dppo_token_logprob_noalloc(const dppo_head_shape* shape,
  * algorithms; the paper names them without formulas, these are this library's readings):
  *   ratio_level = DPPO_RATIO_SEQUENCE: one ratio per sequence, exp(mean_n (logp - logp_old)), takes
  *     the place of rho in every token of the sequence (clip and min as above; KL stays per token).
- *     It needs the log-probs of a whole sequence before any of its gradients, so the vocabulary
- *     GEMM runs one extra forward pass over all tokens first.
+ *     It needs the log-probs of a whole sequence before any of its gradients. With
+ *     max_seq_tokens > 0 (the caller's upper bound on the loss tokens of one sequence; loss_cu
+ *     lives on the device and the call never reads it back) and a workspace that holds two sets
+ *     of per-chunk regions with chunks of at least max_seq_tokens tokens, the forward of chunk
+ *     c + 1 runs ahead of the backward of chunk c and the work stays three GEMMs per token; a
+ *     sequence that breaks the promise sets DPPO_HEAD_SEQ_TOO_LONG. With max_seq_tokens = 0, or a
+ *     workspace too small for that, the vocabulary GEMM runs one extra forward pass over all
+ *     tokens first (unless a single chunk holds the batch).
  *   aggregation = DPPO_AGG_TOKEN_SUM: the per-sequence term is sum_n l_n instead of the mean; with
  *     weights from dppo_token_norm_coef this is the token-level normalisation of the decoupled-clip
  *     objective (clip_lo != clip_hi is the decoupled clip itself). seq_loss then holds the sums.
@@ -252,6 +263,7 @@ typedef struct {
     int32_t recompute_logits;
     int32_t ratio_level;   /* DPPO_RATIO_TOKEN (Eq. 1) or DPPO_RATIO_SEQUENCE */
     int32_t aggregation;   /* DPPO_AGG_SEQ_MEAN (Eq. 1) or DPPO_AGG_TOKEN_SUM */
+    int32_t max_seq_tokens; /* sequence-level ratio only: upper bound on C_s, or 0 = unknown */
 } dppo_loss_params;
 
 int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* p, int32_t S,

@@ -50,10 +50,10 @@ class HeadShape(ctypes.Structure):
 class LossParams(ctypes.Structure):
     _fields_ = [("clip_lo", c_float), ("clip_hi", c_float), ("beta", c_float),
                 ("accumulate_dW", c_int32), ("recompute_logits", c_int32),
-                ("ratio_level", c_int32), ("aggregation", c_int32)]
+                ("ratio_level", c_int32), ("aggregation", c_int32), ("max_seq_tokens", c_int32)]
 
 
-HEAD_BAD_TARGET, HEAD_BAD_POSITION = 1, 2     # bits of the LM-head calls' device status word
+HEAD_BAD_TARGET, HEAD_BAD_POSITION, HEAD_SEQ_TOO_LONG = 1, 2, 4     # bits of the LM-head calls' device status word
 RATIO_LEVELS = {"token": 0, "sequence": 1}
 AGGREGATIONS = {"seq_mean": 0, "token_sum": 1}
 
@@ -271,14 +271,15 @@ def _shape(H, W, N) -> HeadShape:
     return HeadShape(T, N, D, V, _dtype_code(H))
 
 
-def dppo_workspace_bytes(T: int, N: int, D: int, V: int, dtype_code: int, want_backward: bool) -> int:
+def dppo_workspace_bytes(T: int, N: int, D: int, V: int, dtype_code: int, want_backward) -> int:
+    """want_backward: False / 0, True / 1, or 2 (backward with the sequence-level ratio and max_seq_tokens)."""
     shape = HeadShape(T, N, D, V, dtype_code)
-    return int(load().dppo_workspace_bytes(ctypes.byref(shape), 1 if want_backward else 0))
+    return int(load().dppo_workspace_bytes(ctypes.byref(shape), int(want_backward)))
 
 
-def dppo_workspace_min_bytes(T: int, N: int, D: int, V: int, dtype_code: int, want_backward: bool) -> int:
+def dppo_workspace_min_bytes(T: int, N: int, D: int, V: int, dtype_code: int, want_backward) -> int:
     shape = HeadShape(T, N, D, V, dtype_code)
-    return int(load().dppo_workspace_min_bytes(ctypes.byref(shape), 1 if want_backward else 0))
+    return int(load().dppo_workspace_min_bytes(ctypes.byref(shape), int(want_backward)))
 
 
 def alloc_workspace(nbytes: int, device) -> torch.Tensor:
@@ -325,7 +326,7 @@ def dppo_loss_fwd_bwd(H, W, ids, loss_pos, loss_cu, seq_adv, seq_coef, logp_old,
                       recompute_logits: bool = False, ws: Optional[torch.Tensor] = None,
                       dH: Optional[torch.Tensor] = None, out: Optional[dict] = None,
                       ratio_level: str = "token", aggregation: str = "seq_mean",
-                      status: Optional[torch.Tensor] = None) -> dict:
+                      status: Optional[torch.Tensor] = None, max_seq_tokens: int = 0) -> dict:
     """Returns dict(loss[1], logp[N], seq_loss[S], stats[4], dH[T,D], dW[V,D]) of device tensors.
     status: optional int32[1] device tensor for the device-side status word (DPPO_HEAD_BAD_*)."""
     lib = load()
@@ -334,7 +335,7 @@ def dppo_loss_fwd_bwd(H, W, ids, loss_pos, loss_cu, seq_adv, seq_coef, logp_old,
     S = loss_cu.numel() - 1
     shape = _shape(H, W, N)
     if ws is None:
-        ws = alloc_workspace(lib.dppo_workspace_bytes(ctypes.byref(shape), 1), device)
+        ws = alloc_workspace(lib.dppo_workspace_bytes(ctypes.byref(shape), 2 if max_seq_tokens > 0 else 1), device)
     f32 = dict(dtype=torch.float32, device=device)
     if out is None:
         out = dict(loss=torch.empty(1, **f32), logp=torch.empty(N, **f32), seq_loss=torch.empty(max(S, 1), **f32),
@@ -346,7 +347,7 @@ def dppo_loss_fwd_bwd(H, W, ids, loss_pos, loss_cu, seq_adv, seq_coef, logp_old,
             raise ValueError("accumulate_dW needs the dW buffer to accumulate into")
         dW = torch.empty(W.shape, **f32)
     p = LossParams(clip_lo, clip_hi, beta, 1 if accumulate_dW else 0, 1 if recompute_logits else 0,
-                   RATIO_LEVELS[ratio_level], AGGREGATIONS[aggregation])
+                   RATIO_LEVELS[ratio_level], AGGREGATIONS[aggregation], int(max_seq_tokens))
     st = lib.dppo_loss_fwd_bwd(ctypes.byref(shape), ctypes.byref(p), S, _ptr(H), _ptr(W), _ptr(ids), _ptr(loss_pos),
                                _ptr(loss_cu), _ptr(seq_adv), _ptr(seq_coef), _ptr(logp_old), _ptr(logp_ref),
                                _ptr(out["loss"]), _ptr(out["logp"]), _ptr(out["seq_loss"]), _ptr(out["stats"]),

@@ -78,7 +78,8 @@ struct WsPlan {
     int32_t Vp, n_tiles, n_cp;     // padded vocabulary, row tiles of the vocabulary GEMM, chunk rows
     int64_t n_chunks;
     size_t es, zs;                 // element sizes of H/W and of the stored logits / gradient entries
-    size_t fixed_bytes, row_bytes; // bytes independent of / proportional to the chunk size
+    size_t fixed_bytes, chunk_bytes; // bytes of the per-call regions / of one set of per-chunk regions
+    int sets;                      // sets of per-chunk regions (2: the forward of chunk c + 1 runs ahead of the backward of chunk c)
     // region offsets
     size_t o_wt, o_logp, o_ell, o_kl, o_clip, o_seq, o_sratio, o_hc, o_hct, o_part, o_zg, o_gt, o_y, o_rowc, o_zy, o_lse, o_c;
     size_t o_bref, o_mx, o_scale, o_redo_list, o_redo_sum, o_redo_count, o_dwpart;   // bf16 backward only
@@ -92,8 +93,9 @@ int32_t round_up32(int64_t x, int32_t a) { return (int32_t)((x + a - 1) / a * a)
 // reads 256 such rows per slice), so such chunk sizes get 64 elements of padding per row.
 int64_t hct_pitch(int dtype, int32_t n_cp) { return dtype == 1 && n_cp % 2048 == 0 ? (int64_t)n_cp + 64 : (int64_t)n_cp; }
 
-// Lays the workspace out for chunk size n_cp (multiple of CHUNK_ALIGN).
-void layout(const dppo_head_shape& s, bool bwd, int32_t n_cp, WsPlan& p) {
+// Lays the workspace out for chunk size n_cp (multiple of CHUNK_ALIGN): the per-call regions, then `sets`
+// copies of the per-chunk regions (the offsets are those of set 0; set i lies i * chunk_bytes further on).
+void layout(const dppo_head_shape& s, bool bwd, int32_t n_cp, WsPlan& p, int sets = 1) {
     p.es = s.dtype == 1 ? 2 : 4;
     p.zs = p.es;
     p.Vp = round_up32(s.V, mfma_vocab_tile());   // whole vocabulary tiles: the logits epilogue stores unconditionally
@@ -129,7 +131,9 @@ void layout(const dppo_head_shape& s, bool bwd, int32_t n_cp, WsPlan& p) {
     p.o_redo_list = take(per_tok);
     p.o_redo_sum = take(per_tok);
     p.o_redo_count = take(per_tok ? 4 : 0);
-    p.total = off;
+    p.chunk_bytes = off - p.fixed_bytes;
+    p.sets = sets;
+    p.total = p.fixed_bytes + (size_t)sets * p.chunk_bytes;
 }
 
 // Chunk size for N loss tokens: balanced chunks of at most CHUNK_MAX tokens, their number chosen so
@@ -182,21 +186,23 @@ int check_min_workspace(const dppo_head_shape& s, bool bwd, size_t ws_bytes) {
 }
 
 // Picks the largest chunk that fits `ws_bytes` (at most the balanced target chunk).
-int plan_for(const dppo_head_shape& s, bool bwd, size_t ws_bytes, int cus, WsPlan& p) {
+int plan_for(const dppo_head_shape& s, bool bwd, size_t ws_bytes, int cus, WsPlan& p, int sets = 1) {
     const int32_t target = target_chunk(s.N, s.D, s.dtype == 1 ? 2 : 4, cus);
-    layout(s, bwd, target, p);
+    layout(s, bwd, target, p, sets);
     if (p.total > ws_bytes) {
         WsPlan q;
-        layout(s, bwd, CHUNK_ALIGN, q);
-        if (q.total > ws_bytes)
+        layout(s, bwd, CHUNK_ALIGN, q, sets);
+        if (q.total > ws_bytes) {
+            if (sets > 1) return DPPO_ERR_WORKSPACE;   // the caller falls back to one set: no message
             return fail(DPPO_ERR_WORKSPACE, "workspace of %zu bytes is below the minimum of %zu", ws_bytes, q.total);
+        }
         int32_t lo = 1, hi = target / CHUNK_ALIGN;   // in units of CHUNK_ALIGN: lo fits, hi does not
         while (hi - lo > 1) {
             const int32_t mid = (lo + hi) / 2;
-            layout(s, bwd, mid * CHUNK_ALIGN, q);
+            layout(s, bwd, mid * CHUNK_ALIGN, q, sets);
             if (q.total <= ws_bytes) lo = mid; else hi = mid;
         }
-        layout(s, bwd, lo * CHUNK_ALIGN, p);
+        layout(s, bwd, lo * CHUNK_ALIGN, p, sets);
     }
     p.n_chunks = s.N > 0 ? ceil_div(s.N, p.n_cp) : 0;
     return DPPO_OK;
@@ -210,7 +216,8 @@ struct Regions {
     template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(base + off); }
 };
 
-// Forward statistics of one chunk: Hc, targets, log-probs, lse. With keep_z the chunk's logits
+// Forward statistics of one chunk: Hc, targets, log-probs, lse. `ws` is the base of the set of
+// per-chunk regions to use (the workspace itself for set 0); no per-call region is touched. With keep_z the chunk's logits
 // stay in the workspace for the backward pass: as float32 logits (float32 path, which also gets
 // HcT), or as bf16 exponentials against the per-token reference left in the bref region (bf16 path).
 int chunk_forward(const dppo_head_shape& s, const WsPlan& p, char* ws, const void* H, const void* W,
@@ -438,14 +445,15 @@ int dppo_mfma_rate_probe(int random_operands, int iters, float* out, int32_t out
 size_t dppo_workspace_bytes(const dppo_head_shape* shape, int want_backward) {
     if (validate_shape(shape) != DPPO_OK) return 0;
     WsPlan p;
-    layout(*shape, want_backward != 0, target_chunk(shape->N, shape->D, shape->dtype == 1 ? 2 : 4, DEFAULT_CUS), p);
+    layout(*shape, want_backward != 0, target_chunk(shape->N, shape->D, shape->dtype == 1 ? 2 : 4, DEFAULT_CUS), p,
+           want_backward == 2 ? 2 : 1);
     return p.total;
 }
 
 size_t dppo_workspace_min_bytes(const dppo_head_shape* shape, int want_backward) {
     if (validate_shape(shape) != DPPO_OK) return 0;
     WsPlan p;
-    layout(*shape, want_backward != 0, CHUNK_ALIGN, p);
+    layout(*shape, want_backward != 0, CHUNK_ALIGN, p, want_backward == 2 ? 2 : 1);
     return p.total;
 }
 
@@ -526,8 +534,24 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
     int cus = DEFAULT_CUS;
     if (s.dtype == 1 && (rc = mfma_setup(&cus)) != DPPO_OK) return rc;
     WsPlan p;
-    rc = plan_for(s, true, ws_bytes, cus, p);
-    if (rc != DPPO_OK) return rc;
+    // Sequence-level ratio: a sequence's ratio needs all its log-probs before any of its gradients.
+    // With two sets of per-chunk regions the forward of chunk c + 1 runs ahead of the backward of
+    // chunk c, which is enough when no sequence is longer than a chunk (it then ends inside the
+    // chunk after the one it starts in). Otherwise: one forward-only pass over every chunk first.
+    bool ahead = false;
+    if (lp->ratio_level == DPPO_RATIO_SEQUENCE && s.N > 0 && lp->max_seq_tokens > 0) {
+        WsPlan p2;
+        if (plan_for(s, true, ws_bytes, cus, p2, 2) == DPPO_OK && lp->max_seq_tokens <= p2.n_cp) {
+            p = p2;
+            ahead = true;
+        }
+    }
+    if (!ahead) {
+        rc = plan_for(s, true, ws_bytes, cus, p);
+        if (rc != DPPO_OK) return rc;
+        // a single chunk holds every sequence whole: its own forward serves
+        ahead = lp->ratio_level == DPPO_RATIO_SEQUENCE && p.n_chunks == 1;
+    }
 
     hipStream_t st = (hipStream_t)stream;
     char* w = reinterpret_cast<char*>(ws);
@@ -545,75 +569,84 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
         if (s.N > 0) launch_transpose_w(s.dtype, W, s.V, s.D, p.Vp, w + p.o_wt, st);
     }
 
+    const bool recompute = lp->recompute_logits != 0;
+    const bool seq_level = lp->ratio_level == DPPO_RATIO_SEQUENCE && s.N > 0;
     float* seq_ratio = reinterpret_cast<float*>(w + p.o_sratio);
-    if (lp->ratio_level == DPPO_RATIO_SEQUENCE && s.N > 0) {
-        // a sequence's ratio needs all its log-probs, and a sequence may straddle chunks: one
-        // forward-only pass over every chunk first
-        for (int64_t n0 = 0; n0 < s.N; n0 += p.n_cp) {
-            ChunkView cv;
-            cv.n0 = n0;
-            cv.n_c = (int32_t)((s.N - n0) < p.n_cp ? (s.N - n0) : p.n_cp);
-            cv.n_cp = round_up32(cv.n_c, CHUNK_ALIGN);
-            if (int rc = chunk_forward(s, p, w, H, W, ids, loss_pos, cv, false, logp_all, nullptr, status, st)) return rc;
-        }
-        launch_seq_ratio(loss_cu, S, logp_all, logp_old, seq_ratio, st);
+    auto view = [&](int64_t c) {
+        ChunkView cv;
+        cv.n0 = c * p.n_cp;
+        cv.n_c = (int32_t)((s.N - cv.n0) < p.n_cp ? (s.N - cv.n0) : p.n_cp);
+        cv.n_cp = round_up32(cv.n_c, CHUNK_ALIGN);
+        return cv;
+    };
+    // per-chunk regions of chunk c: set c & 1 when the forward runs ahead, else the only set
+    auto regions = [&](int64_t c) { return w + (p.sets == 2 ? (size_t)(c & 1) * p.chunk_bytes : 0); };
+
+    if (seq_level && !ahead) {
+        for (int64_t c = 0; c < p.n_chunks; ++c)
+            if (int rc2 = chunk_forward(s, p, w, H, W, ids, loss_pos, view(c), false, logp_all, nullptr, status, st)) return rc2;
+        launch_seq_ratio(loss_cu, S, logp_all, logp_old, seq_ratio, 0, s.N, nullptr, st);
     }
 
-    bool first = true;
-    for (int64_t n0 = 0; n0 < s.N; n0 += p.n_cp) {
-        ChunkView cv;
-        cv.n0 = n0;
-        cv.n_c = (int32_t)((s.N - n0) < p.n_cp ? (s.N - n0) : p.n_cp);
-        cv.n_cp = round_up32(cv.n_c, CHUNK_ALIGN);
-        const bool recompute = lp->recompute_logits != 0;
-        if (int rc = chunk_forward(s, p, w, H, W, ids, loss_pos, cv, s.dtype == 0 || !recompute, logp_all, nullptr, status, st)) return rc;
+    // forward of chunk c: statistics and log-probs, and what the backward needs of its logits;
+    // with the forward running ahead, also the ratios of the sequences that end in it
+    auto forward = [&](int64_t c) -> int {
+        const ChunkView cv = view(c);
+        if (int rc2 = chunk_forward(s, p, regions(c), H, W, ids, loss_pos, cv, s.dtype == 0 || !recompute, logp_all, nullptr, status, st))
+            return rc2;
+        if (ahead) launch_seq_ratio(loss_cu, S, logp_all, logp_old, seq_ratio, cv.n0, cv.n0 + cv.n_c, status, st);
+        return DPPO_OK;
+    };
 
+    auto backward = [&](int64_t c, bool first) -> int {
+        const ChunkView cv = view(c);
+        char* wc = regions(c);
         TokenLossArgs ta;
         ta.loss_cu = loss_cu; ta.S = S; ta.seq_adv = seq_adv; ta.seq_coef = seq_coef;
         ta.logp_old = logp_old; ta.logp_ref = logp_ref; ta.logp = logp_all;
         ta.lo = (float)(1.0 - (double)lp->clip_lo); ta.hi = (float)(1.0 + (double)lp->clip_hi); ta.beta = lp->beta;
         ta.ratio_level = lp->ratio_level; ta.aggregation = lp->aggregation; ta.seq_ratio = seq_ratio;
-        ta.c_chunk = reinterpret_cast<float*>(w + p.o_c);
+        ta.c_chunk = reinterpret_cast<float*>(wc + p.o_c);
         ta.ell = ell; ta.kl = kl; ta.clipped = clipf;
         {
             StageTimer tm(DPPO_STAGE_ELEMENTWISE, st);
             launch_token_loss(ta, cv, st);
         }
 
-        const int32_t* y = reinterpret_cast<const int32_t*>(w + p.o_y);
-        const float* lse_c = reinterpret_cast<const float*>(w + p.o_lse);
+        const int32_t* y = reinterpret_cast<const int32_t*>(wc + p.o_y);
+        const float* lse_c = reinterpret_cast<const float*>(wc + p.o_lse);
         // bf16: the chunk region holds either gradient entries (recompute) or exponentials whose
         // row scale goes to the dH epilogue and into the HcT operand of dW; in the blocked layout it
         // serves both GEMMs. float32: row-major G and its transposed copy GT.
-        void* G = w + p.o_zg;
+        void* G = wc + p.o_zg;
         const float* row_scale = nullptr;
         if (s.dtype == 0) {
             StageTimer tm(DPPO_STAGE_GRAD_LOGITS, st);
-            launch_grad_logits_f32(reinterpret_cast<float*>(G), reinterpret_cast<float*>(w + p.o_gt), s.V, p.Vp, y, lse_c,
+            launch_grad_logits_f32(reinterpret_cast<float*>(G), reinterpret_cast<float*>(wc + p.o_gt), s.V, p.Vp, y, lse_c,
                                    ta.c_chunk, cv.n_cp, st);
         } else if (recompute) {
             StageTimer tm(DPPO_STAGE_LOGITS_GEMM, st);
-            const int rc2 = launch_mfma_logits_grad(W, s.V, s.D, w + p.o_hc, cv.n_cp, y, lse_c, ta.c_chunk, G, p.Vp,
+            const int rc2 = launch_mfma_logits_grad(W, s.V, s.D, wc + p.o_hc, cv.n_cp, y, lse_c, ta.c_chunk, G, p.Vp,
                                                     p.Vp, st);
             if (rc2 != DPPO_OK) return rc2;
         } else {
             StageTimer tm(DPPO_STAGE_GRAD_LOGITS, st);
-            float* scale = reinterpret_cast<float*>(w + p.o_scale);
-            launch_softmax_scale(y, reinterpret_cast<const float*>(w + p.o_zy), reinterpret_cast<const float*>(w + p.o_bref),
+            float* scale = reinterpret_cast<float*>(wc + p.o_scale);
+            launch_softmax_scale(y, reinterpret_cast<const float*>(wc + p.o_zy), reinterpret_cast<const float*>(wc + p.o_bref),
                                  lse_c, ta.c_chunk, cv, G, p.Vp, scale, st);
             row_scale = scale;
         }
         if (s.dtype == 1) {
             StageTimer tm(DPPO_STAGE_ELEMENTWISE, st);
-            launch_scale_transpose_bf16(w + p.o_hc, row_scale, cv.n_cp, s.D, w + p.o_hct, hct_pitch(1, cv.n_cp), st);
+            launch_scale_transpose_bf16(wc + p.o_hc, row_scale, cv.n_cp, s.D, wc + p.o_hct, hct_pitch(1, cv.n_cp), st);
         }
 
         // dH rows of the chunk: diag(row_scale) G[n_c, Vp] * WT[D, Vp]^T, scattered to the loss rows of dH
         StoreSpec oh;
         oh.out_bf16 = s.dtype == 1; oh.accumulate = 0; oh.ldc = s.D;
         // the scatter goes through the chunk's clamped rows, so it stays inside dH whatever loss_pos holds
-        if (loss_pos) { oh.C = dH; oh.row_map = reinterpret_cast<const int32_t*>(w + p.o_rowc); oh.row_base = 0; }
-        else { oh.C = reinterpret_cast<char*>(dH) + (size_t)n0 * s.D * p.es; oh.row_map = nullptr; oh.row_base = 0; }
+        if (loss_pos) { oh.C = dH; oh.row_map = reinterpret_cast<const int32_t*>(wc + p.o_rowc); oh.row_base = 0; }
+        else { oh.C = reinterpret_cast<char*>(dH) + (size_t)cv.n0 * s.D * p.es; oh.row_map = nullptr; oh.row_base = 0; }
         // dW[v, d] (+)= sum_n G[n, v] HcT[d, n]
         StoreSpec ow;
         ow.C = dW; ow.ldc = s.D; ow.out_bf16 = 0; ow.accumulate = (first && !lp->accumulate_dW) ? 0 : 1;
@@ -625,16 +658,30 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
             }
             {
                 StageTimer tm(DPPO_STAGE_DW_GEMM, st);
-                launch_mfma_dw(cus, G, p.Vp, w + p.o_hct, hct_pitch(1, cv.n_cp), cv.n_cp, s.V, s.D, ow,
+                launch_mfma_dw(cus, G, p.Vp, wc + p.o_hct, hct_pitch(1, cv.n_cp), cv.n_cp, s.V, s.D, ow,
                                reinterpret_cast<float*>(w + p.o_dwpart), st);
             }
         } else {
             launch_gemm_plain_f32(reinterpret_cast<const float*>(G), p.Vp, reinterpret_cast<const float*>(w + p.o_wt),
                                   p.Vp, cv.n_c, s.D, p.Vp, oh, st);
-            launch_gemm_plain_f32(reinterpret_cast<const float*>(w + p.o_gt), cv.n_cp,
-                                  reinterpret_cast<const float*>(w + p.o_hct), cv.n_cp, s.V, s.D, cv.n_cp, ow, st);
+            launch_gemm_plain_f32(reinterpret_cast<const float*>(wc + p.o_gt), cv.n_cp,
+                                  reinterpret_cast<const float*>(wc + p.o_hct), cv.n_cp, s.V, s.D, cv.n_cp, ow, st);
         }
-        first = false;
+        return DPPO_OK;
+    };
+
+    if (ahead) {
+        if (int rc2 = forward(0)) return rc2;
+        for (int64_t c = 0; c < p.n_chunks; ++c) {
+            if (c + 1 < p.n_chunks)
+                if (int rc2 = forward(c + 1)) return rc2;
+            if (int rc2 = backward(c, c == 0)) return rc2;
+        }
+    } else {
+        for (int64_t c = 0; c < p.n_chunks; ++c) {
+            if (int rc2 = forward(c)) return rc2;
+            if (int rc2 = backward(c, c == 0)) return rc2;
+        }
     }
 
     SeqReduceArgs ra;

@@ -96,9 +96,11 @@ struct TokenLossArgs {
     float* ell; float* kl; float* clipped;   // [N] per-token loss, KL, clipped-away flag
 };
 void launch_token_loss(const TokenLossArgs& a, ChunkView cv, hipStream_t st);
-// seq_ratio[s] = exp(mean over the sequence's tokens of logp - logp_old).
+// seq_ratio[s] = exp(mean over the sequence's tokens of logp - logp_old) for the sequences that end
+// in the token range (n_lo, n_hi]; sequences that start below n_lo and end beyond n_hi are flagged
+// in `status` (may be NULL) as DPPO_HEAD_SEQ_TOO_LONG.
 void launch_seq_ratio(const int32_t* loss_cu, int32_t S, const float* logp, const float* logp_old,
-                      float* seq_ratio, hipStream_t st);
+                      float* seq_ratio, int64_t n_lo, int64_t n_hi, int32_t* status, hipStream_t st);
 void launch_token_norm_coef(int32_t Q, int32_t G, const int32_t* comp_len, const float* coef, float* coef_out,
                             hipStream_t st);
 

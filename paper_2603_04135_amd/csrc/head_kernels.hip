@@ -475,14 +475,23 @@ __global__ __launch_bounds__(256) void grad_logits_kernel(void* ZG, GT_* __restr
     }
 }
 
-// One workgroup per packed sequence: exp of the mean log-ratio over its tokens.
+// One workgroup per packed sequence: exp of the mean log-ratio over its tokens, for the sequences
+// that end in the token range (n_lo, n_hi] (all their log-probs are known once the tokens below
+// n_hi are). A sequence that starts below n_lo and ends beyond n_hi is longer than the caller
+// promised: it is flagged in `status` (its ratio is not written by this launch).
 __global__ __launch_bounds__(256) void seq_ratio_kernel(const int32_t* __restrict__ loss_cu, int32_t S,
                                                         const float* __restrict__ logp,
                                                         const float* __restrict__ logp_old,
-                                                        float* __restrict__ seq_ratio) {
+                                                        float* __restrict__ seq_ratio, int64_t n_lo, int64_t n_hi,
+                                                        int32_t* __restrict__ status) {
     __shared__ float r0[256];
     for (int s = blockIdx.x; s < S; s += gridDim.x) {
         const int b = loss_cu[s], e = loss_cu[s + 1];
+        if (e > n_hi) {
+            if (b < n_lo && status && threadIdx.x == 0) atomicOr(status, DPPO_HEAD_SEQ_TOO_LONG);
+            continue;
+        }
+        if (e <= n_lo) continue;
         float x = 0.0f;
         for (int i = b + threadIdx.x; i < e; i += 256) x += logp[i] - logp_old[i];
         r0[threadIdx.x] = x;
@@ -680,10 +689,10 @@ void launch_token_loss(const TokenLossArgs& a, ChunkView cv, hipStream_t st) {
 }
 
 void launch_seq_ratio(const int32_t* loss_cu, int32_t S, const float* logp, const float* logp_old,
-                      float* seq_ratio, hipStream_t st) {
+                      float* seq_ratio, int64_t n_lo, int64_t n_hi, int32_t* status, hipStream_t st) {
     if (S <= 0) return;
     const unsigned blocks = S < 4096 ? (unsigned)S : 4096u;
-    seq_ratio_kernel<<<blocks, 256, 0, st>>>(loss_cu, S, logp, logp_old, seq_ratio);
+    seq_ratio_kernel<<<blocks, 256, 0, st>>>(loss_cu, S, logp, logp_old, seq_ratio, n_lo, n_hi, status);
 }
 
 void launch_token_norm_coef(int32_t Q, int32_t G, const int32_t* comp_len, const float* coef, float* coef_out,

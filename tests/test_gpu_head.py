@@ -208,9 +208,72 @@ def test_objective_variants(lib, ratio_level, aggregation):
             case.logp_ref)
     kw = dict(beta=0.04, ratio_level=ratio_level, aggregation=aggregation, **clip)
     small = lib.dppo_loss_fwd_bwd(*args, ws=lib.alloc_workspace((ws_min + ws_full) // 2, DEV), **kw)
-    assert _same_rows(small["dH"], out["dH"]) and torch.equal(small["seq_loss"], out["seq_loss"])
+    # (the sequence ratios of the chunked call come from the forward-only pass, whose log-probs may differ
+    # in the last bit from those of the pass that also keeps the exponentials)
+    same_seq = torch.equal if ratio_level == "token" else (lambda a, b: torch.allclose(a, b, rtol=1e-5, atol=1e-6))
+    assert _same_rows(small["dH"], out["dH"]) and same_seq(small["seq_loss"], out["seq_loss"])
     rec = lib.dppo_loss_fwd_bwd(*args, recompute_logits=True, **kw)
     assert rel_fro(to_np64(rec["dW"]), ref["dW"]) <= 1e-2 and _same_loss(rec["loss"], out["loss"], ref, case)
+
+
+def test_sequence_ratio_with_forward_running_ahead(lib):
+    """Sequence-level ratio with max_seq_tokens given: the forward of chunk c + 1 runs ahead of the backward of
+    chunk c (one vocabulary GEMM per chunk, not two), the results are those of the single-chunk call, a broken
+    promise is flagged, and without the promise the extra forward pass is taken."""
+    rb = WL.make_rollout("small")
+    sel, pk = oracle_select_pack(rb)
+    sel = dict(sel, adv=np.random.default_rng(12).normal(size=sel["adv"].shape).astype(np.float32))
+    pk = truncate_pack(pk, 6000)
+    case = HeadCase(rb.wl, pk, sel, rb.seed, DEV, logp_noise=0.3)
+    base, _ = case.oracle_logprob()
+    case.set_behaviour_logps(base)
+    cu = case.pk["loss_cu"]
+    longest = int(np.diff(cu).max())
+    assert 512 < longest <= 1024
+    dist = [abs(np.expm1(np.mean(base[cu[i]:cu[i + 1]] - case.logp_old_np[cu[i]:cu[i + 1]]))) for i in range(len(cu) - 1)]
+    kw = dict(beta=0.04, ratio_level="sequence", clip_lo=float(np.median(dist)), clip_hi=float(np.median(dist)) * 1.5)
+    out, ref = _run_case(lib, case, TOL["bf16"], **kw)            # one chunk
+    assert 0.0 < ref["clip_frac"] < 1.0
+    T, N, D, V = case.pk["T"], case.pk["N"], case.wl.D, case.wl.V
+    args = (case.H, case.W, case.ids, case.loss_pos, case.loss_cu, case.seq_adv, case.seq_coef, case.logp_old,
+            case.logp_ref)
+    lo2, hi2 = lib.dppo_workspace_min_bytes(T, N, D, V, 1, 2), lib.dppo_workspace_bytes(T, N, D, V, 1, 2)
+    assert hi2 > lib.dppo_workspace_bytes(T, N, D, V, 1, 1) and lo2 > lib.dppo_workspace_min_bytes(T, N, D, V, 1, 1)
+    # a workspace for two sets of chunks of about 1300 tokens (256 at lo2, 6144 at hi2, linear in between)
+    ws = lib.alloc_workspace(lo2 + (hi2 - lo2) * (1300 - 256) // (6144 - 256), DEV)
+    status = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+
+    def launches(**more):
+        lib.dppo_timing_enable(True)
+        lib.dppo_timing_read(reset=True)
+        res = lib.dppo_loss_fwd_bwd(*args, ws=ws, status=status, **kw, **more)
+        torch.cuda.synchronize()
+        t = lib.dppo_timing_read(reset=True)
+        lib.dppo_timing_enable(False)
+        return res, t["logits_gemm"][1], t["dh_gemm"][1]
+
+    for recompute in (False, True):
+        got, n_logits, n_dh = launches(max_seq_tokens=longest, recompute_logits=recompute)
+        assert n_dh >= 4 and n_logits == (2 if recompute else 1) * n_dh, (n_logits, n_dh)
+        assert int(status.item()) == 0
+        if not recompute:
+            assert _same_rows(got["dH"], out["dH"]) and torch.equal(got["seq_loss"], out["seq_loss"])
+        assert rel_fro(to_np64(got["dW"]), ref["dW"]) <= 1e-2 and rel_fro(to_np64(got["dH"]), ref["dH"]) <= 1e-2
+        assert _same_loss(got["loss"], out["loss"], ref, case)
+        assert np.abs(got["logp"].cpu().numpy() - ref["logp"]).max() <= TOL["bf16"]["logp"]
+    # no promise: one forward-only pass first
+    got, n_logits, n_dh = launches()
+    assert n_logits == 2 * n_dh and int(status.item()) == 0
+    assert _same_rows(got["dH"], out["dH"]) and torch.allclose(got["seq_loss"], out["seq_loss"], rtol=1e-5, atol=1e-6)
+    # a promise the chunks cannot hold falls back to that pass as well
+    got, n_logits, n_dh = launches(max_seq_tokens=4 * longest)
+    assert n_logits == 2 * n_dh and int(status.item()) == 0
+    # a broken promise (sequences of up to 1012 tokens against chunks of 256): flagged, every kernel runs to the end
+    ws = lib.alloc_workspace(lo2, DEV)
+    got, n_logits, n_dh = launches(max_seq_tokens=256)
+    assert n_logits == n_dh == -(-N // 256)
+    assert int(status.item()) & lib.HEAD_SEQ_TOO_LONG
+    assert np.abs(got["logp"].cpu().numpy() - ref["logp"]).max() <= TOL["bf16"]["logp"]
 
 
 def test_objective_variants_fp32(lib):
