@@ -82,3 +82,39 @@ def test_workspace_sizes(lib):
     mn = lib.dppo_workspace_min_bytes(ctypes.byref(hs), 1)
     fwd = lib.dppo_workspace_bytes(ctypes.byref(hs), 0)
     assert 0 < fwd < mn < rec < 40 * 2**30
+
+
+def test_validation_paths_under_host_sanitizers(tmp_path):
+    """Builds the library's host code with AddressSanitizer and UndefinedBehaviorSanitizer (host side only; the
+    device code is compiled as always) together with tests/abi_host_check.c, a plain-C driver that walks every
+    entry point's argument validation and the workspace arithmetic, and runs it: no report, exit status 0."""
+    import shutil
+    import subprocess
+    from concurrent.futures import ThreadPoolExecutor
+
+    import torch
+    from paper_2603_04135_amd import build as B
+
+    hipcc = B._hipcc()
+    clang = shutil.which("amdclang") or "/opt/rocm/llvm/bin/clang"
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-omit-frame-pointer",
+           "-Xarch_host", "-fno-sanitize-recover=undefined", "-g"]
+    jobs, objs = [], []
+    for src in B.SOURCES:
+        obj = str(tmp_path / src.replace(".hip", ".o"))
+        objs.append(obj)
+        jobs.append([hipcc, *B.COMMON_FLAGS, *B.PER_FILE_FLAGS.get(src, []), *san, "-c", os.path.join(B.CSRC, src), "-o", obj])
+    chk = str(tmp_path / "abi_host_check.o")
+    jobs.append([clang, "-std=c11", "-Wall", "-Wextra", "-pedantic", "-Werror", "-g", "-fsanitize=address,undefined",
+                 "-fno-sanitize-recover=undefined", "-I", B.INCLUDE, "-c", os.path.join(ROOT, "tests", "abi_host_check.c"), "-o", chk])
+    with ThreadPoolExecutor(max_workers=4) as ex:
+        list(ex.map(B._run, jobs))
+    exe = str(tmp_path / "abi_host_check")
+    B._run([hipcc, "--offload-arch=gfx950", "-fsanitize=address,undefined", "-fno-gpu-sanitize", *objs, chk, "-o", exe])
+    symbols = subprocess.run(["nm", exe], stdout=subprocess.PIPE, text=True).stdout
+    assert "__asan_report" in symbols and "__ubsan_handle" in symbols, "the sanitizers are not linked in"
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1",
+               DPPO_ABI_CHECK_NO_GPU="0" if torch.cuda.is_available() else "1")
+    proc = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, env=env, timeout=300)
+    assert proc.returncode == 0 and "abi_host_check: ok" in proc.stdout, proc.stdout + proc.stderr
+    assert "runtime error" not in proc.stderr and "AddressSanitizer" not in proc.stderr, proc.stderr
