@@ -40,8 +40,6 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E peak
 # the counters are taken again.
 MEASURED_TRAFFIC_BYTES = {
     ("qwen3_4b", "logits_gemm", False): 2.0 * 19049053 * 1024 + 9734622 * 1024,
-    ("qwen3_4b", "dh_gemm", False): 2.0 * 21310769 * 1024 + 161247 * 1024,
-    ("qwen3_4b", "dw_gemm", False): 2.0 * 22063136 * 1024 + 1560944 * 1024,   # both dispatches
 }
 
 

@@ -88,11 +88,6 @@ struct WsPlan {
 
 int32_t round_up32(int64_t x, int32_t a) { return (int32_t)((x + a - 1) / a * a); }
 
-// Row pitch (elements) of the transposed hidden-state chunk HcT[D, n_cp] of the bf16 path: a pitch
-// that is a multiple of 4 KB sends all rows of a k-slice to the same few L2 channels (the dW GEMM
-// reads 256 such rows per slice), so such chunk sizes get 64 elements of padding per row.
-int64_t hct_pitch(int dtype, int32_t n_cp) { return dtype == 1 && n_cp % 2048 == 0 ? (int64_t)n_cp + 64 : (int64_t)n_cp; }
-
 // Lays the workspace out for chunk size n_cp (multiple of CHUNK_ALIGN): the per-call regions, then `sets`
 // copies of the per-chunk regions (the offsets are those of set 0; set i lies i * chunk_bytes further on).
 void layout(const dppo_head_shape& s, bool bwd, int32_t n_cp, WsPlan& p, int sets = 1) {
@@ -105,7 +100,7 @@ void layout(const dppo_head_shape& s, bool bwd, int32_t n_cp, WsPlan& p, int set
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, REGION_ALIGN); return o; };
     const size_t N = (size_t)s.N;
-    p.o_wt = take(bwd ? (size_t)s.D * p.Vp * p.es : 0);
+    p.o_wt = take(!bwd ? 0 : s.dtype == 1 ? gemm_b_blocked_elems(s.D, p.Vp) * p.es : (size_t)s.D * p.Vp * p.es);
     p.o_logp = take(bwd ? N * 4 : 0);   // log-probs of the batch when the caller wants none back
     p.o_ell = take(bwd ? N * 4 : 0);
     p.o_kl = take(bwd ? N * 4 : 0);
@@ -115,7 +110,7 @@ void layout(const dppo_head_shape& s, bool bwd, int32_t n_cp, WsPlan& p, int set
     p.o_dwpart = take(bwd && s.dtype == 1 ? mfma_dw_partial_bytes() : 0);
     p.fixed_bytes = off;
     p.o_hc = take((size_t)n_cp * s.D * p.es);
-    p.o_hct = take(bwd ? (size_t)(n_cp + 64) * s.D * p.es : 0);   // room for hct_pitch of any chunk
+    p.o_hct = take(!bwd ? 0 : s.dtype == 1 ? gemm_b_blocked_elems(s.D, n_cp) * p.es : (size_t)n_cp * s.D * p.es);
     p.o_part = take((size_t)p.n_tiles * n_cp * 8);
     p.o_zg = take(need_z ? (size_t)n_cp * p.Vp * p.zs : 0);
     p.o_gt = take(bwd && s.dtype == 0 ? (size_t)n_cp * p.Vp * p.zs : 0);   // transposed copy: float32 path only
@@ -638,7 +633,7 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
         }
         if (s.dtype == 1) {
             StageTimer tm(DPPO_STAGE_ELEMENTWISE, st);
-            launch_scale_transpose_bf16(wc + p.o_hc, row_scale, cv.n_cp, s.D, wc + p.o_hct, hct_pitch(1, cv.n_cp), st);
+            launch_scale_transpose_bf16(wc + p.o_hc, row_scale, cv.n_cp, s.D, wc + p.o_hct, st);
         }
 
         // dH rows of the chunk: diag(row_scale) G[n_c, Vp] * WT[D, Vp]^T, scattered to the loss rows of dH
@@ -658,7 +653,7 @@ int dppo_loss_fwd_bwd(const dppo_head_shape* shape, const dppo_loss_params* lp, 
             }
             {
                 StageTimer tm(DPPO_STAGE_DW_GEMM, st);
-                launch_mfma_dw(cus, G, p.Vp, wc + p.o_hct, hct_pitch(1, cv.n_cp), cv.n_cp, s.V, s.D, ow,
+                launch_mfma_dw(cus, G, p.Vp, wc + p.o_hct, cv.n_cp, s.V, s.D, ow,
                                reinterpret_cast<float*>(w + p.o_dwpart), st);
             }
         } else {

@@ -48,7 +48,15 @@ void launch_fill_zero(void* p, size_t bytes, hipStream_t st);
 void launch_gather_rows(int dtype, const void* H, const int32_t* ids, const int32_t* loss_pos,
                         int64_t T, int32_t D, int32_t V, ChunkView cv, void* Hc, void* HcT,
                         int32_t* y, int32_t* rowc, int32_t* status, hipStream_t st);
-// WT[D, Vp] = transpose of W[V, D], columns v >= V zero.
+// Blocked layout of the B operand of the dH and dW GEMMs (WT, HcT): blocks of GEMM_B_BLOCK_ROWS rows x
+// GEMM_B_BLOCK_K columns of a [rows, K] matrix, block (i, j) at (i * K / GEMM_B_BLOCK_K + j) blocks from
+// the start, row-major inside; the rows are padded to whole blocks (the pad rows are never written and only
+// reach output columns that are not stored).
+constexpr int GEMM_B_BLOCK_ROWS = 256, GEMM_B_BLOCK_K = 64;
+inline size_t gemm_b_blocked_elems(int64_t rows, int64_t K) {
+    return (size_t)((rows + GEMM_B_BLOCK_ROWS - 1) / GEMM_B_BLOCK_ROWS * GEMM_B_BLOCK_ROWS) * (size_t)K;
+}
+// WT = transpose of W[V, D], columns v >= V zero: row-major [D, Vp] (float32) or blocked (bfloat16, K = Vp).
 void launch_transpose_w(int dtype, const void* W, int32_t V, int32_t D, int32_t Vp, void* WT,
                         hipStream_t st);
 // zy[n] = Hc[n] . W[y[n]] in fp32; also copied to bref[n] and *flag cleared where not NULL.
@@ -76,10 +84,8 @@ void launch_exp_redo_rows(const int32_t* redo_count, const int32_t* redo_list, f
 // scale[n] E[n, v] = c[n] (1[v == y[n]] - softmax[n, v]).
 void launch_softmax_scale(const int32_t* y, const float* zy, const float* bref, const float* lse, const float* c,
                           ChunkView cv, void* E, int64_t lde, float* scale, hipStream_t st);
-// HcT[D, n_cp] (row pitch ld_hct >= n_cp elements, a multiple of 8) = transpose of
-// diag(scale) Hc[n_cp, D] in bf16 (scale NULL = 1).
-void launch_scale_transpose_bf16(const void* Hc, const float* scale, int32_t n_cp, int32_t D, void* HcT,
-                                 int64_t ld_hct, hipStream_t st);
+// HcT = transpose of diag(scale) Hc[n_cp, D] in bf16 (scale NULL = 1), in the blocked B-operand layout (K = n_cp).
+void launch_scale_transpose_bf16(const void* Hc, const float* scale, int32_t n_cp, int32_t D, void* HcT, hipStream_t st);
 // fp32 path: row statistics straight from stored logits Z[n_cp, ldz].
 void launch_row_stats_f32(const float* Z, int64_t ldz, int32_t V, const int32_t* y, ChunkView cv,
                           float* lse_chunk, float* logp_out, float* lse_out, hipStream_t st);
@@ -157,16 +163,17 @@ int launch_mfma_logits_grad(const void* W, int32_t V, int32_t D, const void* Hc,
                             const int32_t* y, const float* lse, const float* c, void* G, int64_t ldg,
                             int32_t Vp, hipStream_t st);
 // dH rows of a chunk: C[n_c, D] = diag(row_scale) G[n_c, Vp] WT[D, Vp]^T with G in the blocked chunk
-// layout (pitch Vp); row_scale may be NULL (= 1). `partial`: as for launch_mfma_dw.
+// layout (pitch Vp) and WT in the blocked B-operand layout; row_scale may be NULL (= 1). `partial`: as for
+// launch_mfma_dw.
 void launch_mfma_dh(int cus, const void* G, int32_t Vp, const void* WT, int32_t n_c, int32_t D, const float* row_scale,
                     const StoreSpec& out, float* partial, hipStream_t st);
-// dW of a chunk: C[V, D] (+)= G^T HcT^T = sum_n G[n, v] HcT[d, n] (HcT row pitch ld_hct), G read k-major from the
-// same blocks.
+// dW of a chunk: C[V, D] (+)= G^T HcT^T = sum_n G[n, v] HcT[d, n] (HcT in the blocked B-operand layout, K = n_cp),
+// G read k-major from the same blocks.
 // `partial` is scratch of mfma_dw_partial_bytes() bytes (or NULL): with it, the tiles of a
 // sparsely filled last round are split along K over the idle compute units (cus = compute units
 // of the device).
 size_t mfma_dw_partial_bytes();
-void launch_mfma_dw(int cus, const void* G, int32_t Vp, const void* HcT, int64_t ld_hct, int32_t n_cp, int32_t V, int32_t D,
+void launch_mfma_dw(int cus, const void* G, int32_t Vp, const void* HcT, int32_t n_cp, int32_t V, int32_t D,
                     const StoreSpec& out, float* partial, hipStream_t st);
 
 // Benchmark aid: device array of 12 counters (3 GEMM stages x {prologue, main loop, epilogue cycles, tiles})

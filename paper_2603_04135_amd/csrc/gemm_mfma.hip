@@ -19,6 +19,7 @@ using namespace mfma;
 // is as good (dW) or 0.9 % better (dH) than interleaved rounds.
 typedef PipeCfg<256, 256, 64, 2, 4, 2, 0, 1, 4, 1> CfgBig;
 typedef PipeCfg<256, 256, 64, 2, 4, 2, 0, 1, 1, 1> CfgGrad;
+static_assert(CfgGrad::BN == GEMM_B_BLOCK_ROWS && CfgGrad::BK == GEMM_B_BLOCK_K, "blocked B operand = the tile's slices");
 
 // Dynamic LDS of a kernel: the operand slices, or the epilogue's staging area if that is larger.
 template <class Cfg, class Epi>
@@ -34,7 +35,7 @@ constexpr int lds_request() {
 std::atomic<unsigned long long*> g_phase_counters{nullptr};
 enum { PHASE_LOGITS = 0, PHASE_DH = 1, PHASE_DW = 2 };
 
-template <class Cfg, int AM = A_ROWS, int MAP = WG_ROUNDS, class Epi>
+template <class Cfg, int AM = A_ROWS, int MAP = WG_ROUNDS, int BL = B_ROWS, class Epi>
 void launch(const void* A, int64_t lda, const void* B, int64_t ldb, int M, int N, int K, const Epi& epi,
             hipStream_t st, int tile0 = 0, int n_tiles = -1, int k_parts = 1, int phase_stage = -1) {
     const int tiles_m = (int)ceil_div(M, Cfg::BM), tiles_n = (int)ceil_div(N, Cfg::BN);
@@ -42,7 +43,7 @@ void launch(const void* A, int64_t lda, const void* B, int64_t ldb, int M, int N
     if (n_tiles <= 0) return;
     unsigned long long* phase = phase_stage >= 0 && k_parts == 1 ? g_phase_counters.load() : nullptr;
     if (phase) phase += 4 * phase_stage;
-    gemm_nt_kernel<Cfg, Epi, AM, MAP><<<dim3(n_tiles * k_parts), dim3(Cfg::NT), lds_request<Cfg, Epi>(), st>>>(
+    gemm_nt_kernel<Cfg, Epi, AM, MAP, BL><<<dim3(n_tiles * k_parts), dim3(Cfg::NT), lds_request<Cfg, Epi>(), st>>>(
         reinterpret_cast<const uint16_t*>(A), lda, reinterpret_cast<const uint16_t*>(B), ldb, M, N, K, tiles_m,
         tiles_n, tile0, k_parts, epi, phase);
 }
@@ -84,9 +85,9 @@ __global__ __launch_bounds__(256) void sum_partial_tiles_kernel(const float* __r
     }
 }
 
-template <class Cfg, class Epi, int AM = A_ROWS, int MAP = WG_ROUNDS>
+template <class Cfg, class Epi, int AM = A_ROWS, int MAP = WG_ROUNDS, int BL = B_ROWS>
 hipError_t allow_lds() {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_kernel<Cfg, Epi, AM, MAP>),
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_kernel<Cfg, Epi, AM, MAP, BL>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_request<Cfg, Epi>());
 }
 
@@ -110,8 +111,8 @@ int mfma_setup(int* compute_units) {
     DeviceState& d = g_dev[dev];
     if (!d.done) {
         e = hipDeviceGetAttribute(&d.cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e == hipSuccess) e = allow_lds<CfgGrad, EpiStoreDW, A_BLK_KM, WG_RANGES>();
-        if (e == hipSuccess) e = allow_lds<CfgGrad, EpiStoreDH, A_BLK_ROWS, WG_RANGES>();
+        if (e == hipSuccess) e = allow_lds<CfgGrad, EpiStoreDW, A_BLK_KM, WG_RANGES, B_BLK>();
+        if (e == hipSuccess) e = allow_lds<CfgGrad, EpiStoreDH, A_BLK_ROWS, WG_RANGES, B_BLK>();
         if (e == hipSuccess) e = allow_lds<CfgBig, EpiLogits>();
         if (e == hipSuccess) e = allow_lds<CfgBig, EpiLogitsExp>();
         if (e == hipSuccess) e = allow_lds<CfgBig, EpiLogitsGrad>();
@@ -184,19 +185,19 @@ void launch_mfma_dh(int cus, const void* G, int32_t Vp, const void* WT, int32_t 
     int tail;
     const int parts = tail_split(cus, tiles, Vp / CfgGrad::BK, partial, tail);
     if (parts == 1) {
-        launch<CfgGrad, A_BLK_ROWS, WG_RANGES>(G, Vp, WT, Vp, n_c, D, Vp, e, st, 0, -1, 1, PHASE_DH);
+        launch<CfgGrad, A_BLK_ROWS, WG_RANGES, B_BLK>(G, Vp, WT, 0, n_c, D, Vp, e, st, 0, -1, 1, PHASE_DH);
         return;
     }
-    launch<CfgGrad, A_BLK_ROWS, WG_RANGES>(G, Vp, WT, Vp, n_c, D, Vp, e, st, 0, tiles - tail, 1, PHASE_DH);
+    launch<CfgGrad, A_BLK_ROWS, WG_RANGES, B_BLK>(G, Vp, WT, 0, n_c, D, Vp, e, st, 0, tiles - tail, 1, PHASE_DH);
     EpiStoreDH ep = e;
     ep.partial = partial;
-    launch<CfgGrad, A_BLK_ROWS, WG_RANGES>(G, Vp, WT, Vp, n_c, D, Vp, ep, st, tiles - tail, tail, parts);
+    launch<CfgGrad, A_BLK_ROWS, WG_RANGES, B_BLK>(G, Vp, WT, 0, n_c, D, Vp, ep, st, tiles - tail, tail, parts);
     sum_partial_tiles_kernel<CfgGrad><<<dim3(tail, CfgGrad::BM / 16), 256, 0, st>>>(
         partial, tiles - tail, parts, tiles_m, tiles_n, nullptr, out.ldc, n_c, D, 0, reinterpret_cast<uint16_t*>(out.C),
         out.row_map, out.row_base, row_scale);
 }
 
-void launch_mfma_dw(int cus, const void* G, int32_t Vp, const void* HcT, int64_t ld_hct, int32_t n_cp, int32_t V, int32_t D,
+void launch_mfma_dw(int cus, const void* G, int32_t Vp, const void* HcT, int32_t n_cp, int32_t V, int32_t D,
                     const StoreSpec& out, float* partial, hipStream_t st) {
     EpiStoreDW e{reinterpret_cast<float*>(out.C), nullptr, out.ldc, out.accumulate, nullptr, 0, nullptr, nullptr};
     const int tiles_m = (int)ceil_div(V, CfgGrad::BM), tiles_n = (int)ceil_div(D, CfgGrad::BN);
@@ -204,13 +205,13 @@ void launch_mfma_dw(int cus, const void* G, int32_t Vp, const void* HcT, int64_t
     int tail;
     const int parts = tail_split(cus, tiles, n_cp / CfgGrad::BK, partial, tail);
     if (parts == 1) {
-        launch<CfgGrad, A_BLK_KM, WG_RANGES>(G, Vp, HcT, ld_hct, V, D, n_cp, e, st, 0, -1, 1, PHASE_DW);
+        launch<CfgGrad, A_BLK_KM, WG_RANGES, B_BLK>(G, Vp, HcT, 0, V, D, n_cp, e, st, 0, -1, 1, PHASE_DW);
         return;
     }
-    launch<CfgGrad, A_BLK_KM, WG_RANGES>(G, Vp, HcT, ld_hct, V, D, n_cp, e, st, 0, tiles - tail, 1, PHASE_DW);
+    launch<CfgGrad, A_BLK_KM, WG_RANGES, B_BLK>(G, Vp, HcT, 0, V, D, n_cp, e, st, 0, tiles - tail, 1, PHASE_DW);
     EpiStoreDW ep = e;
     ep.partial = partial;
-    launch<CfgGrad, A_BLK_KM, WG_RANGES>(G, Vp, HcT, ld_hct, V, D, n_cp, ep, st, tiles - tail, tail, parts);
+    launch<CfgGrad, A_BLK_KM, WG_RANGES, B_BLK>(G, Vp, HcT, 0, V, D, n_cp, ep, st, tiles - tail, tail, parts);
     sum_partial_tiles_kernel<CfgGrad><<<dim3(tail, CfgGrad::BM / 16), 256, 0, st>>>(
         partial, tiles - tail, parts, tiles_m, tiles_n, reinterpret_cast<float*>(out.C), out.ldc, V, D, out.accumulate,
         nullptr, nullptr, 0, nullptr);

@@ -141,6 +141,13 @@ struct PipeCfg {
 // lanes touches, and the two groups of a half-wave (same columns, k-rows 8 apart), fall into
 // different banks.
 enum { A_ROWS = 0, A_BLK_ROWS = 1, A_BLK_KM = 2 };
+// Layouts of the B operand ([N, K], K contiguous in both):
+//   B_ROWS  row-major, ldb = row pitch;
+//   B_BLK   in blocks of BN rows x BK columns, block (tile column tn, slice kt) at ((tn * K / BK) + kt) * BN * BK,
+//           row-major inside: the slice a tile loads is one contiguous 32 KB run instead of BN pieces of
+//           128 bytes a row pitch apart (with pitches of 64 KB to 300 KB that costs 5 % of the dH main loop's
+//           cycles and 2.5 % of dW's). N is padded to whole blocks; ldb is not used.
+enum { B_ROWS = 0, B_BLK = 1 };
 constexpr int BLK_R = 64, BLK_C = 256;
 __host__ __device__ __forceinline__ size_t blk_offset(int64_t r, int64_t c, int64_t ld) {
     return (size_t)(r / BLK_R) * BLK_R * ld + (size_t)(c / BLK_C) * (BLK_R * BLK_C) + (r % BLK_R) * BLK_C + c % BLK_C;
@@ -167,7 +174,7 @@ __host__ __device__ __forceinline__ void tile_coords(int tile, int tiles_m, int 
 // and part p of a tile computes the k-slices [p KT / k_parts, (p + 1) KT / k_parts) of it
 // (k_parts = 1: whole tiles).
 enum { WG_ROUNDS = 0, WG_RANGES = 1 };
-template <class Cfg, class Epi, int AM = A_ROWS, int MAP = WG_ROUNDS>
+template <class Cfg, class Epi, int AM = A_ROWS, int MAP = WG_ROUNDS, int BL = B_ROWS>
 __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __restrict__ A, int64_t lda,
                                                           const uint16_t* __restrict__ B, int64_t ldb, int M,
                                                           int N, int K, int tiles_m, int tiles_n, int tile0,
@@ -235,6 +242,10 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
         }
         const int row = ci / CPR, pc = ci % CPR;
         const int kc = pc ^ swz<CPR, Cfg::SWZ>(row);
+        if (BL == B_BLK && !isA) {
+            pl[i] = B + ((size_t)tn * (K / Cfg::BK) * Cfg::BN + row) * Cfg::BK + kc * 8;
+            continue;
+        }
         int r = (isA ? bm0 : bn0) + row;
         const int lim = isA ? M : N;
         r = r < lim ? r : lim - 1;
@@ -256,7 +267,7 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_nt_kernel(const uint16_t* __rest
         const bool isA = i >= Cfg::B_LD;
         const int ii = isA ? i - Cfg::B_LD : i;
         char* dst = smem + (isA ? bufa * Cfg::A_BYTES : Cfg::B_RING + bufb * Cfg::B_BYTES) + (ii * Cfg::NW + wave) * 1024;
-        const uint16_t* src = isA ? pl[ii] + koff_a : pl[Cfg::A_LD + ii] + koff;
+        const uint16_t* src = isA ? pl[ii] + koff_a : pl[Cfg::A_LD + ii] + (BL == B_BLK ? koff * Cfg::BN : koff);
         __builtin_amdgcn_global_load_lds(DPPO_GPTR(src), DPPO_LPTR(dst), 16, 0, 0);
     };
 

@@ -302,10 +302,13 @@ __global__ void softmax_scale_kernel(const int32_t* __restrict__ y, const float*
 // bf16 transpose by 16-byte accesses: dstT[c, r] = scale[r] * src[r, c] (scale NULL = 1) for
 // r < rows_out, c < cols; source rows >= rows_valid read as zero. cols and rows_out are
 // multiples of 64, all pointers and pitches multiples of 8 elements. A 64 x 64 tile goes through
-// LDS; every thread loads and stores whole 8-element vectors.
+// LDS; every thread loads and stores whole 8-element vectors. dstT is row-major with pitch
+// ld_dstT, or (blocked != 0) the blocked B-operand layout of the MFMA GEMMs with ld_dstT = rows_out
+// columns in all: blocks of GEMM_B_BLOCK_ROWS rows x GEMM_B_BLOCK_K columns, block (i, j) at
+// (i * ld_dstT / GEMM_B_BLOCK_K + j) blocks from the start (a 64 x 64 tile is then one contiguous 8 KB run).
 __global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __restrict__ src, int64_t ld_src,
                                                              int32_t rows_valid, const float* __restrict__ scale,
-                                                             uint16_t* __restrict__ dstT, int64_t ld_dstT) {
+                                                             uint16_t* __restrict__ dstT, int64_t ld_dstT, int blocked) {
     __shared__ uint16_t tile[64][64 + 2];
     const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
     const int vec = threadIdx.x & 7, line = threadIdx.x >> 3;
@@ -340,7 +343,13 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __r
 #pragma unroll
         for (int k = 0; k < 4; ++k)
             w[k] = (uint32_t)tile[vec * 8 + 2 * k][cc] | ((uint32_t)tile[vec * 8 + 2 * k + 1][cc] << 16);
-        *reinterpret_cast<uint4*>(dstT + (int64_t)(c0 + cc) * ld_dstT + r0 + vec * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+        static_assert(GEMM_B_BLOCK_K == 64, "a 64-column tile = one block column");
+        const int64_t drow = c0 + cc;
+        const int64_t off = blocked ? ((drow / GEMM_B_BLOCK_ROWS) * (ld_dstT / GEMM_B_BLOCK_K) + r0 / GEMM_B_BLOCK_K) *
+                                              (int64_t)(GEMM_B_BLOCK_ROWS * GEMM_B_BLOCK_K) +
+                                          (drow % GEMM_B_BLOCK_ROWS) * GEMM_B_BLOCK_K + vec * 8
+                                    : drow * ld_dstT + r0 + vec * 8;
+        *reinterpret_cast<uint4*>(dstT + off) = make_uint4(w[0], w[1], w[2], w[3]);
     }
 }
 
@@ -613,13 +622,9 @@ void launch_gather_rows(int dtype, const void* H, const int32_t* ids, const int3
 
 void launch_transpose_w(int dtype, const void* W, int32_t V, int32_t D, int32_t Vp, void* WT, hipStream_t st) {
     dim3 grid((unsigned)ceil_div(D, 64), (unsigned)ceil_div(Vp, 64));
-    if (dtype == 1 && D % 64 == 0 && Vp % 64 == 0) {
+    if (dtype == 1) {      // D and Vp are multiples of 64 on the bf16 path
         transpose_bf16_kernel<<<grid, 256, 0, st>>>(reinterpret_cast<const uint16_t*>(W), D, V, nullptr,
-                                                    reinterpret_cast<uint16_t*>(WT), Vp);
-    } else if (dtype == 1) {
-        gather_transpose_kernel<uint16_t><<<grid, 256, 0, st>>>(reinterpret_cast<const uint16_t*>(W), D, nullptr, 0,
-                                                                0, V, V, D, Vp, D, nullptr, 0,
-                                                                reinterpret_cast<uint16_t*>(WT), Vp);
+                                                    reinterpret_cast<uint16_t*>(WT), Vp, 1);
     } else {
         gather_transpose_kernel<float><<<grid, 256, 0, st>>>(reinterpret_cast<const float*>(W), D, nullptr, 0, 0, V,
                                                              V, D, Vp, D, nullptr, 0, reinterpret_cast<float*>(WT),
@@ -666,11 +671,10 @@ void launch_softmax_scale(const int32_t* y, const float* zy, const float* bref, 
                                                                            reinterpret_cast<uint16_t*>(E), lde, scale);
 }
 
-void launch_scale_transpose_bf16(const void* Hc, const float* scale, int32_t n_cp, int32_t D, void* HcT,
-                                 int64_t ld_hct, hipStream_t st) {
+void launch_scale_transpose_bf16(const void* Hc, const float* scale, int32_t n_cp, int32_t D, void* HcT, hipStream_t st) {
     dim3 grid((unsigned)(D / 64), (unsigned)(n_cp / 64));
     transpose_bf16_kernel<<<grid, 256, 0, st>>>(reinterpret_cast<const uint16_t*>(Hc), D, n_cp, scale,
-                                                reinterpret_cast<uint16_t*>(HcT), ld_hct);
+                                                reinterpret_cast<uint16_t*>(HcT), n_cp, 1);
 }
 
 void launch_combine_logprob(const float2* part, int32_t n_tiles, const float* zy, ChunkView cv, float* lse_chunk,
