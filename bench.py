@@ -39,7 +39,9 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E peak
 # gives). Keyed by (workload, kernel, recompute); an entry is deleted when that kernel changes, until
 # the counters are taken again.
 MEASURED_TRAFFIC_BYTES = {
-    ("qwen3_4b", "logits_gemm", False): 2.0 * 19049053 * 1024 + 9734622 * 1024,
+    ("qwen3_4b", "logits_gemm", False): 2.0 * 19078238 * 1024 + 9734993 * 1024,
+    ("qwen3_4b", "dh_gemm", False): 2.0 * 21319216 * 1024 + 161247 * 1024,
+    ("qwen3_4b", "dw_gemm", False): 2.0 * 22005603 * 1024 + 1560944 * 1024,   # both dispatches
 }
 
 
