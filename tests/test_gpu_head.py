@@ -276,6 +276,37 @@ def test_sequence_ratio_with_forward_running_ahead(lib):
     assert np.abs(got["logp"].cpu().numpy() - ref["logp"]).max() <= TOL["bf16"]["logp"]
 
 
+@pytest.mark.parametrize("case_seed", [11, 12, 13, 14, 15, 16, 17, 18])
+def test_random_shapes_with_tails(lib, case_seed):
+    """Seeded random shapes (D any multiple of 64, so the 256-row blocks of the backward GEMMs' B operands are
+    partly filled; V and N with tails), a workspace of random size between the minimum and the recommended one
+    (several chunks), both gradient modes, and the sequence-level ratio with the forward running ahead."""
+    rng = np.random.default_rng(case_seed)
+    D = int(rng.choice([64, 128, 192, 320, 448, 576, 1024, 1088]))
+    V = int(rng.integers(100, 6000))
+    case = _case("small", int(rng.integers(150, 2600)), seed=int(rng.integers(1, 10**6)), dtype="bf16", D=D, V=V)
+    T, N = case.pk["T"], case.pk["N"]
+    out, ref = _run_case(lib, case, TOL["bf16"])
+    args = (case.H, case.W, case.ids, case.loss_pos, case.loss_cu, case.seq_adv, case.seq_coef, case.logp_old,
+            case.logp_ref)
+    lo, hi = lib.dppo_workspace_min_bytes(T, N, D, V, 1, True), lib.dppo_workspace_bytes(T, N, D, V, 1, True)
+    ws = lib.alloc_workspace(int(lo + (hi - lo) * float(rng.uniform(0.0, 0.9))), DEV)
+    for recompute in (False, True):
+        got = lib.dppo_loss_fwd_bwd(*args, ws=ws, recompute_logits=recompute)
+        assert rel_fro(to_np64(got["dW"]), ref["dW"]) <= 1e-2 and rel_fro(to_np64(got["dH"]), ref["dH"]) <= 1e-2
+        assert np.abs(got["logp"].cpu().numpy() - ref["logp"]).max() <= TOL["bf16"]["logp"]
+        _assert_loss(float(got["loss"].item()), ref, case, TOL["bf16"]["loss"])
+    ref_s = case.oracle_loss(ratio_level="sequence")
+    lo2, hi2 = lib.dppo_workspace_min_bytes(T, N, D, V, 1, 2), lib.dppo_workspace_bytes(T, N, D, V, 1, 2)
+    ws2 = lib.alloc_workspace(int(lo2 + (hi2 - lo2) * float(rng.uniform(0.3, 1.0))), DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    got = lib.dppo_loss_fwd_bwd(*args, ws=ws2, ratio_level="sequence", status=status,
+                                max_seq_tokens=int(np.diff(case.pk["loss_cu"]).max()))
+    assert int(status.item()) == 0
+    assert rel_fro(to_np64(got["dW"]), ref_s["dW"]) <= 1e-2 and rel_fro(to_np64(got["dH"]), ref_s["dH"]) <= 1e-2
+    _assert_loss(float(got["loss"].item()), ref_s, case, TOL["bf16"]["loss"])
+
+
 def test_objective_variants_fp32(lib):
     case = _case("tiny", None)
     for ratio_level, aggregation in VARIANTS:
